@@ -1,0 +1,165 @@
+/*
+ * libdba - the per-timestep Dynamic Beam Allocation (DBA) step of lexically
+ * constrained beam search on AMD MI355X (gfx950), behind a C ABI.
+ *
+ * Method: Post & Vilar (2018), "Fast Lexically Constrained Decoding with
+ * Dynamic Beam Allocation for Neural Machine Translation":
+ *   Alg. 1  the beam-search loop this step plugs into (decoder-step -> kbest);
+ *   Alg. 2  kbest-DBA: candidates from three sources, then allocate;
+ *   Sec. 3.1 candidate set, constraint bookkeeping, unwinding;
+ *   Sec. 3.2 bank allocation and adjustment;
+ *   Sec. 3.3 finishing (no end-of-sentence before all constraints are met).
+ *
+ * Conventions
+ *   - "host" / "device" is said for every pointer.  Device pointers are plain
+ *     hipMalloc-style addresses on the current device; no framework types.
+ *   - The library allocates no device memory: state, history and scratch are
+ *     carved from a caller-provided workspace.
+ *   - dba_step only enqueues work on the stream given at init and returns;
+ *     nothing is synchronised before dba_finalize / dba_get_state.
+ *   - Every function returns DBA_OK (0) or a negative code; none throws or
+ *     aborts.  dba_last_error gives the text of the last failure.
+ *   - One ctx is used from one host thread at a time.
+ *
+ * Limits (checked by dba_init): 1 <= k <= 64; constraint tokens per sentence
+ * <= 64; k*V*(Cmax+1) must fit the packed sort key (k*V <= 2^(32-bits(Cmax)),
+ * e.g. k*V <= 2^25 at 64 tokens, 2^26 at 32 tokens).
+ */
+#ifndef DBA_H
+#define DBA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DBA_API __attribute__((visibility("default")))
+
+#define DBA_OK 0
+#define DBA_EINVAL (-1) /* bad argument                                   */
+#define DBA_ESTATE (-2) /* call out of order (e.g. more than N steps)     */
+#define DBA_EHIP (-3)   /* a HIP runtime call failed                      */
+#define DBA_ENOMEM (-4) /* workspace too small / host allocation failed   */
+
+#define DBA_MAX_BEAM 64
+#define DBA_MAX_CONS_TOKENS 64
+
+#define DBA_FLAG_FINISHED 1 /* hypothesis has generated end-of-sentence    */
+#define DBA_FLAG_DEAD 2     /* empty beam slot                             */
+
+typedef struct dba_ctx dba_ctx;
+
+/*
+ * Bytes of device workspace dba_init needs for a job of B sentences, beam k,
+ * vocabulary V and at most N steps (Alg. 1 inputs N, k).  max_cons_tokens is
+ * an upper bound on the constraint tokens of any sentence (0..64).
+ * Returns 0 if an argument is out of range.
+ */
+DBA_API size_t dba_workspace_bytes(int B, int k, int V, int N, int max_cons_tokens);
+
+/*
+ * decoder-init of Alg. 1 plus the constraints of every sentence (Sec. 3:
+ * word and phrasal constraints; C = total tokens).
+ *
+ *   out              host: receives the new ctx (host object, free with dba_destroy)
+ *   B, k, V, N       batch, beam size, target vocabulary size, max output length
+ *   eos_id, pad_id   end-of-sentence id; id written into empty slots and used
+ *                    as the sole continuation of finished hypotheses
+ *   cons_tokens      host [total tokens]   all constraint token ids, phrase after phrase
+ *   phrase_offsets   host [total phrases+1] phrase p = cons_tokens[phrase_offsets[p] .. phrase_offsets[p+1])
+ *   sent_offsets     host [B+1]            sentence b owns phrases sent_offsets[b] .. sent_offsets[b+1]
+ *                    (a sentence may have none).  The three arrays are copied; the caller may free them.
+ *   workspace_dev    device, 256-byte aligned, >= dba_workspace_bytes(...) bytes; owned by the
+ *                    caller, must stay valid and untouched until dba_destroy
+ *   hip_stream       a hipStream_t (NULL = default stream); all work of this ctx is enqueued on it
+ *
+ * The initial beam of every sentence is one live, empty hypothesis in slot 0
+ * with score +0.0; the other k-1 slots are empty.
+ * Errors: DBA_EINVAL for sizes < 1, k > 64, k > V, ids outside [0,V),
+ * eos_id == pad_id, a constraint token equal to eos_id or pad_id, an empty
+ * phrase, offsets not starting at 0 / not non-decreasing, more than 64 tokens
+ * in a sentence, the key-width limit above, a misaligned workspace;
+ * DBA_ENOMEM if workspace_bytes is too small; DBA_EHIP on a runtime failure.
+ */
+DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int pad_id,
+             const int32_t *cons_tokens, const int32_t *phrase_offsets,
+             const int32_t *sent_offsets, void *workspace_dev, size_t workspace_bytes,
+             void *hip_stream);
+
+/*
+ * One call of kbest-DBA (Alg. 2) for all B sentences.
+ *
+ *   logp_dev        device [B,k,V] fp32, row-major, 4-byte aligned, read only; row h of
+ *                   sentence b holds the log-probabilities of extending the hypothesis in
+ *                   beam slot h of the previous step's output (the "scores" matrix of
+ *                   Sec. 2 before the hypothesis score is added).  Must stay valid until
+ *                   the stream has passed this step.
+ *   out_token_dev   device [B,k] int32: token of each new beam slot, best first (pad_id if empty)
+ *   out_backptr_dev device [B,k] int32: beam slot of the parent hypothesis (-1 if empty)
+ *   out_score_dev   device [B,k] fp32 : cumulative score = parent score + logp, one fp32 add
+ *                   (-inf if empty)
+ *   out_flags_dev   device [B,k] uint8: DBA_FLAG_* bits; may be NULL
+ *
+ * Any of the first three outputs may also be NULL (the beam is kept inside the
+ * ctx anyway).  Asynchronous.  Errors: DBA_EINVAL (NULL ctx / logp), DBA_ESTATE
+ * after N steps, DBA_EHIP if the launch fails.
+ */
+DBA_API int dba_step(dba_ctx *ctx, const float *logp_dev, int32_t *out_token_dev,
+             int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev);
+
+/*
+ * End of Alg. 1 with Sec. 3.3 and the length normalisation of Sec. 4: for each
+ * sentence the completed hypothesis (end-of-sentence generated, hence all
+ * constraints met) with the best score/length, traced back through the
+ * recorded steps.  Synchronises the stream.
+ *
+ *   out_tokens_host host [B,N] int32, pad_id-filled beyond the length
+ *   out_len_host    host [B]   int32, tokens incl. end-of-sentence
+ *   out_score_host  host [B]   fp32, raw cumulative score of the returned hypothesis
+ *   out_status_host host [B]   int32, 1 = a completed hypothesis was found; 0 = none (the
+ *                   returned one is then the live slot with most constraints met,
+ *                   then best score)
+ * May be called after any number of steps, more than once.
+ */
+DBA_API int dba_finalize(dba_ctx *ctx, int32_t *out_tokens_host, int32_t *out_len_host,
+                 float *out_score_host, int32_t *out_status_host);
+
+/*
+ * Copy the current beam state to the host (synchronises the stream).  Every
+ * pointer is host [B,k] and may be NULL.  met_mask bit i = constraint token i
+ * of the sentence (in the order given to dba_init) is marked met (Sec. 3.1);
+ * inprog_phrase = index within the sentence of the phrase under way (-1 none),
+ * inprog_pos = how many of its tokens are met.
+ */
+DBA_API int dba_get_state(dba_ctx *ctx, float *score_host, uint64_t *met_mask_host,
+                  int32_t *inprog_phrase_host, int32_t *inprog_pos_host, int32_t *length_host,
+                  uint8_t *flags_host);
+
+/* Number of dba_step calls made so far (or DBA_EINVAL). */
+DBA_API int dba_steps_done(const dba_ctx *ctx);
+
+/* Frees the host-side ctx only; device memory belongs to the caller. */
+DBA_API void dba_destroy(dba_ctx *ctx);
+
+/* Text of the last error on this ctx, or of the last failed dba_init of the
+ * calling thread if ctx is NULL.  Never NULL. */
+DBA_API const char *dba_last_error(const dba_ctx *ctx);
+
+/*
+ * Diagnostic: runs the device-side bank allocation of Sec. 3.2 alone, on one
+ * wavefront, for n_cases independent problems.
+ *   k_host [n_cases], C_host [n_cases] (0..64), cnt_host [n_cases][65] candidates per bank,
+ *   alloc_host [n_cases][65] receives the slots per bank.  All host pointers; the call
+ * stages them through `scratch_dev` (device, >= n_cases*132*4 bytes) on `hip_stream`
+ * and synchronises.
+ */
+DBA_API int dba_debug_allocate(int n_cases, const int32_t *k_host, const int32_t *C_host,
+                       const int32_t *cnt_host, int32_t *alloc_host, void *scratch_dev,
+                       size_t scratch_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBA_H */

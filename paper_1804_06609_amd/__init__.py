@@ -1,0 +1,10 @@
+"""MI355X-native Dynamic Beam Allocation step (Post & Vilar 2018, Alg. 2).
+
+The product is libdba.so (HIP, gfx950) declared in include/dba.h; this package
+is its ctypes binding.  PyTorch is used by callers only to own device memory
+and streams.
+"""
+from .binding import (DBA_EHIP, DBA_EINVAL, DBA_ENOMEM, DBA_ESTATE, DBA_FLAG_DEAD,  # noqa: F401
+                      DBA_FLAG_FINISHED, DBA_MAX_BEAM, DBA_MAX_CONS_TOKENS, DBA_OK, DbaError,
+                      dba_debug_allocate, dba_destroy, dba_finalize, dba_get_state, dba_init,
+                      dba_last_error, dba_step, dba_steps_done, dba_workspace_bytes, load)

@@ -1,0 +1,34 @@
+"""Builds libdba.so (HIP, gfx950 only) next to this file."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libdba.so")
+SOURCES = [os.path.join(CSRC, "dba.hip")]
+DEPS = SOURCES + [os.path.join(CSRC, f) for f in ("dba_kernels.hpp", "wave_topk.hpp")] + [
+    os.path.join(os.path.dirname(HERE), "include", "dba.h")]
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-fvisibility=hidden",
+    # packed fp32 VALU forms are kept off on the test machines
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def build(force: bool = True, extra=()) -> str:
+    stale = force or not os.path.exists(LIB) or any(
+        os.path.getmtime(LIB) < os.path.getmtime(d) for d in DEPS)
+    if stale:
+        cmd = [HIPCC] + FLAGS + list(extra) + SOURCES + ["-o", LIB]
+        subprocess.check_call(cmd)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True, extra=sys.argv[1:]))

@@ -1,0 +1,527 @@
+// libdba: C-ABI implementation (see include/dba.h) and the gfx950 kernels' entry points.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "../../include/dba.h"
+#include "dba_kernels.hpp"
+
+using namespace dba;
+
+// ---------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------
+// Grid: one workgroup per beam row.  U = float4 loads each lane keeps in flight per tile.
+template <int U>
+__global__ __launch_bounds__(kBlock) void dba_step_kernel(const StepParams p)
+{
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
+    __shared__ MergeSmem sm;
+
+    const int row = blockIdx.x;
+    const int b = row / p.k;
+    const int h = row - b * p.k;
+    const int lane = lane_id();
+    const int wave = (int)(threadIdx.x >> 6);
+
+    // the row's hypothesis: wave-uniform by construction, made so for the compiler
+    const float prev = __uint_as_float(
+        (uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(p.score_cur[row])));
+    const int fin = __builtin_amdgcn_readfirstlane((int)p.fin_cur[row]);
+
+    RowTop st;
+    st.list = 0;
+    st.kth = 0;
+    st.thr = -INFINITY;
+    if (prev > -INFINITY && !fin) {
+        const int P = p.nphr[b];
+        const int C = p.phr_off[(size_t)b * (kMaxCons + 1) + P];
+        const int nmet = __popcll(p.met_cur[row]);
+        // Sec. 3.3: no end-of-sentence before all constraints are met
+        const int eos_block = __builtin_amdgcn_readfirstlane(nmet < C ? p.eos_id : -1);
+        stream_row<U>(p.logp + (size_t)row * (size_t)p.V, p.V, prev, eos_block,
+                      (uint32_t)h * (uint32_t)p.V, p.k, wave, kWavesPerBlock, st);
+    } else if (prev > -INFINITY && wave == 0 && lane == 0) {
+        // a finished hypothesis stays on the beam: its one continuation is the pad token
+        // at log-prob +0.0, score carried unchanged
+        st.list = make_key(prev + 0.0f, (uint32_t)h * (uint32_t)p.V + (uint32_t)p.pad_id);
+    }
+    sm.wl[wave][lane] = st.list;
+    __syncthreads();
+    if (wave == 0) {
+        u64 acc = st.list;
+        for (int w = 1; w < kWavesPerBlock; ++w) acc = merge_desc(acc, sm.wl[w][lane]);
+        p.rowlists[(size_t)row * kWave + lane] = acc;
+    }
+    if (!p.fused) return;
+
+    // Last workgroup of the sentence to deliver its list runs the merge phase.
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int old = atomicAdd(&p.counters[b], 1u);
+        sm.last = (old == (unsigned int)(p.k - 1)) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!sm.last) return;
+    __threadfence();
+    if (threadIdx.x == 0) p.counters[b] = 0;
+    merge_phase(p, b, sm, reinterpret_cast<u64 *>(dyn_smem));
+}
+
+// Grid: one workgroup per sentence (the two-launch form of the step).
+__global__ __launch_bounds__(kBlock) void dba_merge_kernel(const StepParams p)
+{
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
+    __shared__ MergeSmem sm;
+    merge_phase(p, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
+}
+
+// decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0
+__global__ void dba_init_state_kernel(int B, int k, float *score, u64 *met, int32_t *ipq,
+                                      int32_t *len, uint8_t *fin, unsigned int *counters)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B * k) {
+        score[i] = (i % k == 0) ? 0.0f : -INFINITY;
+        met[i] = 0;
+        ipq[i] = -1;
+        len[i] = 0;
+        fin[i] = 0;
+    }
+    if (i < B) counters[i] = 0;
+}
+
+// End of decoding (Sec. 3.3, length normalisation of Sec. 4): one thread per sentence.
+__global__ void dba_finalize_kernel(int B, int k, int T, int N, int pad_id,
+                                    const int32_t *hist_token, const int32_t *hist_backptr,
+                                    const float *score, const u64 *met, const int32_t *len,
+                                    const uint8_t *fin, int32_t *out_tokens, int32_t *out_len,
+                                    float *out_score, int32_t *out_status)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int32_t *toks = out_tokens + (size_t)b * N;
+    for (int i = 0; i < N; ++i) toks[i] = pad_id;
+    out_len[b] = 0;
+    out_score[b] = -INFINITY;
+    out_status[b] = 0;
+    if (T < 1) return;
+    const size_t o = (size_t)b * k;
+    int best = -1;
+    float bestq = 0.0f;
+    for (int h = 0; h < k; ++h) {
+        if (!(score[o + h] > -INFINITY) || !fin[o + h]) continue;
+        const float q = __fdiv_rn(score[o + h], (float)len[o + h]);
+        if (best < 0 || q > bestq) {
+            best = h;
+            bestq = q;
+        }
+    }
+    if (best >= 0) {
+        out_status[b] = 1;
+    } else {
+        int bestn = -1;
+        for (int h = 0; h < k; ++h) {
+            if (!(score[o + h] > -INFINITY)) continue;
+            const int n = __popcll(met[o + h]);
+            if (best < 0 || n > bestn || (n == bestn && score[o + h] > score[o + best])) {
+                best = h;
+                bestn = n;
+            }
+        }
+        if (best < 0) return;
+    }
+    const int L = len[o + best];
+    out_len[b] = L;
+    out_score[b] = score[o + best];
+    int slot = best;
+    for (int t = T - 1; t >= 0; --t) {
+        const size_t r = ((size_t)t * B + b) * k + slot;
+        if (t < L && t < N) toks[t] = hist_token[r];
+        slot = hist_backptr[r];
+    }
+}
+
+// Diagnostic: the allocation of Sec. 3.2 alone, one wavefront per case.
+__global__ void dba_allocate_kernel(int n_cases, const int32_t *kk, const int32_t *CC,
+                                    const int32_t *cnt, int32_t *alloc)
+{
+    const int i = blockIdx.x;
+    if (i >= n_cases) return;
+    const int lane = lane_id();
+    const int C = CC[i];
+    const int c = cnt[(size_t)i * 65 + lane];
+    const int c64 = cnt[(size_t)i * 65 + 64];
+    int a64;
+    const int a = allocate_wave(kk[i], C, c, c64, a64);
+    alloc[(size_t)i * 65 + lane] = lane <= C ? a : 0;
+    if (lane == 0) alloc[(size_t)i * 65 + 64] = C == 64 ? a64 : 0;
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+namespace {
+
+thread_local char g_init_error[256] = "";
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+    size_t score[2], met[2], ipq[2], len[2], fin[2];
+    size_t cons_tok, phr_off, nphr, rowlists, counters;
+    size_t hist_token, hist_backptr;
+    size_t fin_tokens, fin_len, fin_score, fin_status;
+    size_t total;
+};
+
+Layout make_layout(size_t B, size_t k, size_t N)
+{
+    Layout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    for (int i = 0; i < 2; ++i) {
+        L.score[i] = take(B * k * sizeof(float));
+        L.met[i] = take(B * k * sizeof(u64));
+        L.ipq[i] = take(B * k * sizeof(int32_t));
+        L.len[i] = take(B * k * sizeof(int32_t));
+        L.fin[i] = take(B * k);
+    }
+    L.cons_tok = take(B * kMaxCons * sizeof(int32_t));
+    L.phr_off = take(B * (kMaxCons + 1) * sizeof(int32_t));
+    L.nphr = take(B * sizeof(int32_t));
+    L.rowlists = take(B * k * kWave * sizeof(u64));
+    L.counters = take(B * sizeof(unsigned int));
+    L.hist_token = take(N * B * k * sizeof(int32_t));
+    L.hist_backptr = take(N * B * k * sizeof(int32_t));
+    L.fin_tokens = take(B * N * sizeof(int32_t));
+    L.fin_len = take(B * sizeof(int32_t));
+    L.fin_score = take(B * sizeof(float));
+    L.fin_status = take(B * sizeof(int32_t));
+    L.total = off;
+    return L;
+}
+
+int bits_for(int v)   // bits needed to hold values 0..v
+{
+    int n = 0;
+    while ((1 << n) <= v) ++n;
+    return n;
+}
+
+}  // namespace
+
+struct dba_ctx {
+    int B, k, V, N, eos_id, pad_id;
+    int met_bits;
+    int max_phrases;
+    int steps;
+    int fused;
+    int unroll;
+    size_t dyn_smem;
+    unsigned char *ws;
+    Layout L;
+    hipStream_t stream;
+    char err[256];
+};
+
+namespace {
+
+int fail(dba_ctx *ctx, int code, const char *fmt, ...)
+{
+    char *dst = ctx ? ctx->err : g_init_error;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 256, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool shape_ok(int B, int k, int V, int N, int max_cons)
+{
+    return B >= 1 && k >= 1 && k <= DBA_MAX_BEAM && V >= 1 && N >= 1 && k <= V && max_cons >= 0 &&
+           max_cons <= DBA_MAX_CONS_TOKENS;
+}
+
+template <typename T>
+T *at(dba_ctx *c, size_t off)
+{
+    return reinterpret_cast<T *>(c->ws + off);
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+}  // namespace
+
+extern "C" {
+
+DBA_API size_t dba_workspace_bytes(int B, int k, int V, int N, int max_cons_tokens)
+{
+    if (!shape_ok(B, k, V, N, max_cons_tokens)) return 0;
+    return make_layout((size_t)B, (size_t)k, (size_t)N).total;
+}
+
+DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int pad_id,
+             const int32_t *cons_tokens, const int32_t *phrase_offsets,
+             const int32_t *sent_offsets, void *workspace_dev, size_t workspace_bytes,
+             void *hip_stream)
+{
+    if (!out) return fail(nullptr, DBA_EINVAL, "dba_init: out is NULL");
+    *out = nullptr;
+    if (!shape_ok(B, k, V, N, 0))
+        return fail(nullptr, DBA_EINVAL,
+                    "dba_init: need B,V,N >= 1 and 1 <= k <= %d, k <= V (got B=%d k=%d V=%d N=%d)",
+                    DBA_MAX_BEAM, B, k, V, N);
+    if (eos_id < 0 || eos_id >= V || pad_id < 0 || pad_id >= V || eos_id == pad_id)
+        return fail(nullptr, DBA_EINVAL, "dba_init: eos_id/pad_id must be distinct ids in [0,V)");
+    if (!sent_offsets || !phrase_offsets)
+        return fail(nullptr, DBA_EINVAL, "dba_init: sent_offsets / phrase_offsets is NULL");
+    if (!workspace_dev) return fail(nullptr, DBA_EINVAL, "dba_init: workspace_dev is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % 256 != 0)
+        return fail(nullptr, DBA_EINVAL, "dba_init: workspace_dev must be 256-byte aligned");
+
+    // constraints -> fixed-stride per-sentence tables
+    if (sent_offsets[0] != 0 || phrase_offsets[0] != 0)
+        return fail(nullptr, DBA_EINVAL, "dba_init: offsets must start at 0");
+    std::vector<int32_t> tok((size_t)B * kMaxCons, 0), off((size_t)B * (kMaxCons + 1), 0), nph(B, 0);
+    int max_tokens = 0, max_phrases = 0;
+    for (int b = 0; b < B; ++b) {
+        const int p0 = sent_offsets[b], p1 = sent_offsets[b + 1];
+        if (p1 < p0) return fail(nullptr, DBA_EINVAL, "dba_init: sent_offsets decreases at %d", b);
+        const int t0 = phrase_offsets[p0];
+        int n = 0;
+        for (int p = p0; p < p1; ++p) {
+            const int a = phrase_offsets[p], e = phrase_offsets[p + 1];
+            if (e <= a) return fail(nullptr, DBA_EINVAL, "dba_init: phrase %d is empty or offsets decrease", p);
+            if (a - t0 != n)
+                return fail(nullptr, DBA_EINVAL, "dba_init: phrase offsets of sentence %d are not contiguous", b);
+            if (n + (e - a) > DBA_MAX_CONS_TOKENS)
+                return fail(nullptr, DBA_EINVAL, "dba_init: sentence %d has more than %d constraint tokens", b,
+                            DBA_MAX_CONS_TOKENS);
+            if (!cons_tokens) return fail(nullptr, DBA_EINVAL, "dba_init: cons_tokens is NULL");
+            off[(size_t)b * (kMaxCons + 1) + (p - p0)] = n;
+            for (int i = a; i < e; ++i) {
+                const int w = cons_tokens[i];
+                if (w < 0 || w >= V)
+                    return fail(nullptr, DBA_EINVAL, "dba_init: constraint token %d outside [0,V)", w);
+                if (w == eos_id || w == pad_id)
+                    return fail(nullptr, DBA_EINVAL, "dba_init: eos_id/pad_id cannot be a constraint token");
+                tok[(size_t)b * kMaxCons + n++] = w;
+            }
+        }
+        off[(size_t)b * (kMaxCons + 1) + (p1 - p0)] = n;
+        nph[b] = p1 - p0;
+        if (n > max_tokens) max_tokens = n;
+        if (p1 - p0 > max_phrases) max_phrases = p1 - p0;
+    }
+    const int met_bits = bits_for(max_tokens);
+    if ((unsigned long long)k * (unsigned long long)V > (1ull << (32 - met_bits)))
+        return fail(nullptr, DBA_EINVAL,
+                    "dba_init: k*V = %llu exceeds 2^%d, the coordinate width left by %d constraint tokens",
+                    (unsigned long long)k * V, 32 - met_bits, max_tokens);
+
+    const Layout L = make_layout((size_t)B, (size_t)k, (size_t)N);
+    if (workspace_bytes < L.total)
+        return fail(nullptr, DBA_ENOMEM, "dba_init: workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+
+    dba_ctx *c = new (std::nothrow) dba_ctx;
+    if (!c) return fail(nullptr, DBA_ENOMEM, "dba_init: out of host memory");
+    memset(c, 0, sizeof *c);
+    c->B = B; c->k = k; c->V = V; c->N = N; c->eos_id = eos_id; c->pad_id = pad_id;
+    c->met_bits = met_bits;
+    c->max_phrases = max_phrases;
+    c->steps = 0;
+    c->ws = static_cast<unsigned char *>(workspace_dev);
+    c->L = L;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->fused = env_int("DBA_FUSED", 1) ? 1 : 0;
+    c->unroll = env_int("DBA_UNROLL", 4);
+    int npad = kWave;
+    while (npad < k * (max_phrases + 2)) npad <<= 1;
+    c->dyn_smem = (size_t)npad * sizeof(u64);
+
+    hipError_t e;
+    e = hipMemcpyAsync(at<int32_t>(c, L.cons_tok), tok.data(), tok.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(at<int32_t>(c, L.phr_off), off.data(), off.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(at<int32_t>(c, L.nphr), nph.data(), nph.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) {
+        const int n = B * k;
+        dba_init_state_kernel<<<(n + 255) / 256, 256, 0, c->stream>>>(
+            B, k, at<float>(c, L.score[0]), at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]),
+            at<int32_t>(c, L.len[0]), at<uint8_t>(c, L.fin[0]), at<unsigned int>(c, L.counters));
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);   // host tables are freed on return
+    if (e != hipSuccess) {
+        const int rc = fail(nullptr, DBA_EHIP, "dba_init: HIP error: %s", hipGetErrorString(e));
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return DBA_OK;
+}
+
+DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, int32_t *out_backptr_dev,
+             float *out_score_dev, uint8_t *out_flags_dev)
+{
+    if (!c) return DBA_EINVAL;
+    if (!logp_dev) return fail(c, DBA_EINVAL, "dba_step: logp_dev is NULL");
+    if (reinterpret_cast<uintptr_t>(logp_dev) % 4 != 0)
+        return fail(c, DBA_EINVAL, "dba_step: logp_dev must be 4-byte aligned");
+    if (c->steps >= c->N) return fail(c, DBA_ESTATE, "dba_step: all N=%d steps have been taken", c->N);
+
+    const int cur = c->steps & 1, nxt = cur ^ 1;
+    const Layout &L = c->L;
+    StepParams p;
+    p.B = c->B; p.k = c->k; p.V = c->V;
+    p.eos_id = c->eos_id; p.pad_id = c->pad_id;
+    p.met_bits = c->met_bits;
+    p.fused = c->fused;
+    p.logp = logp_dev;
+    p.score_cur = at<float>(c, L.score[cur]);
+    p.met_cur = at<u64>(c, L.met[cur]);
+    p.ipq_cur = at<int32_t>(c, L.ipq[cur]);
+    p.len_cur = at<int32_t>(c, L.len[cur]);
+    p.fin_cur = at<uint8_t>(c, L.fin[cur]);
+    p.score_nxt = at<float>(c, L.score[nxt]);
+    p.met_nxt = at<u64>(c, L.met[nxt]);
+    p.ipq_nxt = at<int32_t>(c, L.ipq[nxt]);
+    p.len_nxt = at<int32_t>(c, L.len[nxt]);
+    p.fin_nxt = at<uint8_t>(c, L.fin[nxt]);
+    p.cons_tok = at<int32_t>(c, L.cons_tok);
+    p.phr_off = at<int32_t>(c, L.phr_off);
+    p.nphr = at<int32_t>(c, L.nphr);
+    p.rowlists = at<u64>(c, L.rowlists);
+    p.counters = at<unsigned int>(c, L.counters);
+    p.out_token = out_token_dev;
+    p.out_backptr = out_backptr_dev;
+    p.out_score = out_score_dev;
+    p.out_flags = out_flags_dev;
+    const size_t hrow = (size_t)c->steps * c->B * c->k;
+    p.hist_token = at<int32_t>(c, L.hist_token) + hrow;
+    p.hist_backptr = at<int32_t>(c, L.hist_backptr) + hrow;
+
+    const dim3 grid((unsigned)(c->B * c->k)), block(kBlock);
+    const size_t smem = c->fused ? c->dyn_smem : 0;
+    switch (c->unroll) {
+        case 2: dba_step_kernel<2><<<grid, block, smem, c->stream>>>(p); break;
+        case 8: dba_step_kernel<8><<<grid, block, smem, c->stream>>>(p); break;
+        default: dba_step_kernel<4><<<grid, block, smem, c->stream>>>(p); break;
+    }
+    if (!c->fused) dba_merge_kernel<<<dim3((unsigned)c->B), block, c->dyn_smem, c->stream>>>(p);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_step: launch failed: %s", hipGetErrorString(e));
+    c->steps += 1;
+    return DBA_OK;
+}
+
+DBA_API int dba_finalize(dba_ctx *c, int32_t *out_tokens_host, int32_t *out_len_host, float *out_score_host,
+                 int32_t *out_status_host)
+{
+    if (!c) return DBA_EINVAL;
+    if (!out_tokens_host || !out_len_host || !out_score_host || !out_status_host)
+        return fail(c, DBA_EINVAL, "dba_finalize: an output pointer is NULL");
+    const Layout &L = c->L;
+    const int cur = c->steps & 1;
+    dba_finalize_kernel<<<(c->B + 63) / 64, 64, 0, c->stream>>>(
+        c->B, c->k, c->steps, c->N, c->pad_id, at<int32_t>(c, L.hist_token), at<int32_t>(c, L.hist_backptr),
+        at<float>(c, L.score[cur]), at<u64>(c, L.met[cur]), at<int32_t>(c, L.len[cur]),
+        at<uint8_t>(c, L.fin[cur]), at<int32_t>(c, L.fin_tokens), at<int32_t>(c, L.fin_len),
+        at<float>(c, L.fin_score), at<int32_t>(c, L.fin_status));
+    hipError_t e = hipGetLastError();
+    const size_t B = (size_t)c->B;
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(out_tokens_host, at<int32_t>(c, L.fin_tokens), B * c->N * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(out_len_host, at<int32_t>(c, L.fin_len), B * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(out_score_host, at<float>(c, L.fin_score), B * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(out_status_host, at<int32_t>(c, L.fin_status), B * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_finalize: HIP error: %s", hipGetErrorString(e));
+    return DBA_OK;
+}
+
+DBA_API int dba_get_state(dba_ctx *c, float *score_host, uint64_t *met_mask_host, int32_t *inprog_phrase_host,
+                  int32_t *inprog_pos_host, int32_t *length_host, uint8_t *flags_host)
+{
+    if (!c) return DBA_EINVAL;
+    const Layout &L = c->L;
+    const int cur = c->steps & 1;
+    const size_t n = (size_t)c->B * c->k;
+    std::vector<float> score(n);
+    std::vector<int32_t> ipq(n);
+    std::vector<uint8_t> fin(n);
+    hipError_t e = hipMemcpyAsync(score.data(), at<float>(c, L.score[cur]), n * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ipq.data(), at<int32_t>(c, L.ipq[cur]), n * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(fin.data(), at<uint8_t>(c, L.fin[cur]), n, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess && met_mask_host)
+        e = hipMemcpyAsync(met_mask_host, at<u64>(c, L.met[cur]), n * 8, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess && length_host)
+        e = hipMemcpyAsync(length_host, at<int32_t>(c, L.len[cur]), n * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_get_state: HIP error: %s", hipGetErrorString(e));
+    for (size_t i = 0; i < n; ++i) {
+        if (score_host) score_host[i] = score[i];
+        if (inprog_phrase_host) inprog_phrase_host[i] = ipq[i] < 0 ? -1 : (ipq[i] >> 8);
+        if (inprog_pos_host) inprog_pos_host[i] = ipq[i] < 0 ? 0 : (ipq[i] & 255);
+        if (flags_host)
+            flags_host[i] = (uint8_t)((fin[i] ? DBA_FLAG_FINISHED : 0) | (score[i] > -INFINITY ? 0 : DBA_FLAG_DEAD));
+    }
+    return DBA_OK;
+}
+
+DBA_API int dba_steps_done(const dba_ctx *c) { return c ? c->steps : DBA_EINVAL; }
+
+DBA_API void dba_destroy(dba_ctx *c) { delete c; }
+
+DBA_API const char *dba_last_error(const dba_ctx *c) { return c ? c->err : g_init_error; }
+
+DBA_API int dba_debug_allocate(int n_cases, const int32_t *k_host, const int32_t *C_host, const int32_t *cnt_host,
+                       int32_t *alloc_host, void *scratch_dev, size_t scratch_bytes, void *hip_stream)
+{
+    if (n_cases < 1 || !k_host || !C_host || !cnt_host || !alloc_host || !scratch_dev)
+        return fail(nullptr, DBA_EINVAL, "dba_debug_allocate: bad argument");
+    const size_t n = (size_t)n_cases;
+    if (scratch_bytes < n * 132 * 4) return fail(nullptr, DBA_ENOMEM, "dba_debug_allocate: scratch too small");
+    for (size_t i = 0; i < n; ++i)
+        if (k_host[i] < 1 || k_host[i] > DBA_MAX_BEAM || C_host[i] < 0 || C_host[i] > DBA_MAX_CONS_TOKENS)
+            return fail(nullptr, DBA_EINVAL, "dba_debug_allocate: case %zu out of range", i);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int32_t *d_k = static_cast<int32_t *>(scratch_dev);
+    int32_t *d_C = d_k + n;
+    int32_t *d_cnt = d_C + n;
+    int32_t *d_alloc = d_cnt + n * 65;
+    hipError_t e = hipMemcpyAsync(d_k, k_host, n * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(d_C, C_host, n * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(d_cnt, cnt_host, n * 65 * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) {
+        dba_allocate_kernel<<<dim3((unsigned)n_cases), dim3(kWave), 0, s>>>(n_cases, d_k, d_C, d_cnt, d_alloc);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(alloc_host, d_alloc, n * 65 * 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(nullptr, DBA_EHIP, "dba_debug_allocate: HIP error: %s", hipGetErrorString(e));
+    return DBA_OK;
+}
+
+}  // extern "C"

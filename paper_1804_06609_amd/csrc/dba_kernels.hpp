@@ -1,0 +1,510 @@
+// Device side of the DBA step (Post & Vilar 2018, Alg. 2, Sec. 3.1-3.3) for gfx950.
+//
+// Two phases per step:
+//   stream phase  one workgroup per beam row (b,h): a single pass over the V
+//                 log-probs of that row - score add, end-of-sentence mask,
+//                 exact top-64 of the row (which holds the row's best token
+//                 and its share of the sentence's top-k) - written as one
+//                 sorted 64-key list per row;
+//   merge phase   one workgroup per sentence: sentence top-k from the row
+//                 lists, constraint-token gather, state transition add(),
+//                 dedup, banks, allocation with adjustment, selection, new
+//                 beam.  In the fused launch it is run by whichever row
+//                 workgroup of the sentence finishes last.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "wave_topk.hpp"
+
+namespace dba {
+
+constexpr int kMaxBeam = 64;
+constexpr int kMaxCons = 64;          // constraint tokens (and phrases) per sentence
+constexpr int kBlock = 256;           // threads per workgroup
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kSortThresh = 10;       // survivors in one wave-wide test above which a sort+merge beats serial inserts
+
+struct StepParams {
+    int B, k, V;
+    int eos_id, pad_id;
+    int met_bits;                     // width of the bank field in the packed selection key
+    int fused;                        // 1: the last row workgroup of a sentence runs the merge phase
+    const float *logp;                // [B,k,V]
+    // beam before the step
+    const float *score_cur;           // [B,k]  (-inf: empty slot)
+    const u64 *met_cur;               // [B,k]  bit i = constraint token i met
+    const int32_t *ipq_cur;           // [B,k]  phrase under way * 256 + tokens met in it, or -1
+    const int32_t *len_cur;           // [B,k]
+    const uint8_t *fin_cur;           // [B,k]
+    // beam after the step
+    float *score_nxt;
+    u64 *met_nxt;
+    int32_t *ipq_nxt;
+    int32_t *len_nxt;
+    uint8_t *fin_nxt;
+    // constraints
+    const int32_t *cons_tok;          // [B,64]
+    const int32_t *phr_off;           // [B,65] token offset of each phrase, phr_off[b][P] = C
+    const int32_t *nphr;              // [B]
+    // scratch
+    u64 *rowlists;                    // [B*k,64]
+    unsigned int *counters;           // [B] rows of the sentence that have delivered their list
+    // outputs (each may be null)
+    int32_t *out_token, *out_backptr;
+    float *out_score;
+    uint8_t *out_flags;
+    int32_t *hist_token, *hist_backptr;   // row t of the history, [B,k]
+};
+
+struct MergeSmem {
+    u64 wl[kWavesPerBlock][kWave];
+    u64 t1[kWave];
+    u64 rb[kMaxBeam];
+    u64 sel[kMaxBeam];
+    u64 met[kMaxBeam];
+    float prev[kMaxBeam];
+    int ipq[kMaxBeam];
+    int len[kMaxBeam];
+    int tok[kMaxCons];
+    int poff[kMaxCons + 1];
+    int cnt[kMaxCons + 1];
+    int alloc[kMaxCons + 1];
+    int start[kMaxCons + 1];
+    unsigned char fin[kMaxBeam];
+    int nsel;
+    int last;
+};
+
+// ---------------------------------------------------------------------------
+// stream phase
+// ---------------------------------------------------------------------------
+struct RowTop {
+    u64 list;      // this lane's entry of the wave's decreasing top-64
+    u64 kth;       // key at place k-1 (0 while fewer than k entries)
+    float thr;     // score of kth, -inf while fewer than k entries
+};
+
+__device__ __forceinline__ void refresh_threshold(RowTop &st, int kk)
+{
+    st.kth = read_lane(st.list, kk - 1);
+    st.thr = (st.kth == 0) ? -INFINITY : float_from_ord((uint32_t)(st.kth >> 32));
+}
+
+// Wave-wide: every lane offers at most one element (pass = it may belong to the top k).
+__device__ __forceinline__ void consider(RowTop &st, float s, uint32_t flat, bool pass, int kk)
+{
+    u64 m = __ballot(pass);
+    if (m == 0) return;
+    const u64 key = pass ? make_key(s, flat) : 0ull;
+    if (__popcll(m) > kSortThresh) {
+        st.list = merge_desc(st.list, sort64_desc(key));
+    } else {
+        do {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const u64 x = read_lane(key, l);
+            if (x > st.kth) {
+                st.list = insert_desc(st.list, x);
+                st.kth = read_lane(st.list, kk - 1);
+            }
+        } while (m);
+    }
+    refresh_threshold(st, kk);
+}
+
+__device__ __forceinline__ float4 neg_inf4()
+{
+    return make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+}
+
+template <int U>
+__device__ __forceinline__ void load_tile(const float4 *__restrict__ vec, int nv, int tile, int lane,
+                                          float4 (&x)[U])
+{
+    const int base = tile * (kWave * U);
+    if (base + kWave * U <= nv) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[u] = vec[base + u * kWave + lane];
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = base + u * kWave + lane;
+            x[u] = (i < nv) ? vec[i] : neg_inf4();
+        }
+    }
+}
+
+// One wave's share of one row.  s = prev + logp is a single fp32 add; an element
+// is looked at closely only if its sum can still reach the wave's current k-th
+// best (>=: a later element may tie the k-th score and win on the coordinate).
+// Because rounding is monotone, max(prev + x_i) == prev + max(x_i), so one add
+// per float4 suffices for the test.
+template <int U>
+__device__ __forceinline__ void stream_row(const float *__restrict__ row, int V, float prev,
+                                           int eos_block, uint32_t flat_base, int kk, int wave,
+                                           int nwaves, RowTop &st)
+{
+    const int lane = lane_id();
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
+    int head = (int)(((16u - (unsigned)(addr & 15u)) & 15u) >> 2);
+    if (head > V) head = V;
+    const int nv = (V - head) >> 2;
+    const int tail = V - head - (nv << 2);
+    const float4 *__restrict__ vec = reinterpret_cast<const float4 *>(row + head);
+    const int ntiles = (nv + kWave * U - 1) / (kWave * U);
+
+    float4 cur[U], nxt[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) nxt[u] = neg_inf4();
+    int tl = wave;
+    if (tl < ntiles) load_tile<U>(vec, nv, tl, lane, cur);
+    while (tl < ntiles) {
+        const int nx = tl + nwaves;
+        if (nx < ntiles) load_tile<U>(vec, nv, nx, lane, nxt);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float4 x = cur[u];
+            const float m4 = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+            if (__any(prev + m4 >= st.thr)) {
+                const int w0 = head + 4 * ((tl * U + u) * kWave + lane);
+                const float xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float s = prev + xs[c];
+                    const bool pass = (s >= st.thr) && (s > -INFINITY) && (w0 + c != eos_block);
+                    consider(st, s, flat_base + (uint32_t)(w0 + c), pass, kk);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+        tl = nx;
+    }
+    // elements before the first / after the last 16-byte aligned group (rows whose
+    // length or start is not a multiple of four floats)
+    if (wave == 0 && head + tail > 0) {
+        const bool mine = lane < head + tail;
+        const int w = lane < head ? lane : head + (nv << 2) + (lane - head);
+        const float s = mine ? prev + row[w] : -INFINITY;
+        const bool pass = mine && (s >= st.thr) && (s > -INFINITY) && (w != eos_block);
+        consider(st, s, flat_base + (uint32_t)w, pass, kk);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// constraint bookkeeping (Sec. 3.1): in-order phrases, one phrase under way
+// ---------------------------------------------------------------------------
+// Token that phrase j lets the hypothesis place now, or -1: the next token of
+// the phrase under way; the first token of a phrase neither complete nor under way.
+__device__ __forceinline__ int expandable_token(const MergeSmem &sm, u64 met, int ip, int iq, int j)
+{
+    const int o = sm.poff[j];
+    if (j == ip) return sm.tok[o + iq];
+    const int last = sm.poff[j + 1] - 1;
+    if ((met >> last) & 1ull) return -1;
+    return sm.tok[o];
+}
+
+// State after emitting w: advance the phrase under way, or unwind it and let w
+// begin the lowest-index incomplete phrase that starts with w.
+__device__ __forceinline__ void cons_add(const MergeSmem &sm, int P, u64 &met, int &ip, int &iq, int w)
+{
+    if (ip >= 0) {
+        const int o = sm.poff[ip];
+        if (sm.tok[o + iq] == w) {
+            met |= 1ull << (o + iq);
+            ++iq;
+            if (o + iq == sm.poff[ip + 1]) {
+                ip = -1;
+                iq = 0;
+            }
+            return;
+        }
+        met &= ~(((1ull << iq) - 1ull) << o);
+        ip = -1;
+        iq = 0;
+    }
+    for (int j = 0; j < P; ++j) {
+        const int o = sm.poff[j], e = sm.poff[j + 1];
+        if ((met >> (e - 1)) & 1ull) continue;
+        if (sm.tok[o] != w) continue;
+        met |= 1ull << o;
+        if (e - o > 1) {
+            ip = j;
+            iq = 1;
+        }
+        return;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// allocation (Sec. 3.2) on one wavefront, registers only
+// ---------------------------------------------------------------------------
+// Lane x holds bank x (x < 64); bank 64 is carried wave-uniform.  c = candidates
+// in the bank; returns the slots of the lane's bank and writes bank 64's to a64.
+// Base split: floor(k/(C+1)) each, remainder to bank C.  Adjustment: banks with
+// more slots than candidates, in ascending order, keep what they can fill and
+// pass the rest to banks with spare candidates, nearest first, the higher
+// neighbour before the lower, as much as each can take.
+__device__ __forceinline__ int allocate_wave(int k, int C, int c, int c64, int &a64)
+{
+    const int lane = lane_id();
+    const int base = k / (C + 1);
+    const int rem = k - base * (C + 1);
+    int a = (lane <= C) ? base + (lane == C ? rem : 0) : 0;
+    a64 = (C == 64) ? base + rem : 0;
+    if (lane > C) c = 0;
+    if (C < 64) c64 = 0;
+
+    u64 donors = __ballot(a > c);                         // fixed before the hand-outs begin:
+    bool donor64 = a64 > c64;                             // a receiver never becomes a donor
+    for (;;) {
+        int b, e;
+        if (donors != 0) {
+            b = __ffsll((long long)donors) - 1;
+            donors &= donors - 1;
+            e = __builtin_amdgcn_readlane(a - c, b);
+            if (lane == b) a = c;
+        } else if (donor64) {
+            donor64 = false;
+            b = 64;
+            e = a64 - c64;
+            a64 = c64;
+        } else {
+            break;
+        }
+        const int need = max(0, c - a);
+        const int need64 = max(0, c64 - a64);
+        if (__ballot(need > 0) == 0 && need64 == 0) continue;   // nobody can take a slot
+        // lane l looks at distance d = l+1: bank b+d first, then bank b-d
+        const int d = lane + 1;
+        const int xu = b + d, xd = b - d;
+        const int nu = __shfl(need, xu & 63, kWave);
+        const int nd = __shfl(need, xd & 63, kWave);
+        const int up = (xu <= C) ? (xu < 64 ? nu : need64) : 0;
+        const int dn = (xd >= 0) ? nd : 0;
+        const int before = wave_inclusive_sum(up + dn) - (up + dn);
+        const int gu = min(up, max(0, e - before));
+        const int gd = min(dn, max(0, e - before - up));
+        const int from_up = __shfl(gu, (lane - b - 1) & 63, kWave);
+        const int from_dn = __shfl(gd, (b - lane - 1) & 63, kWave);
+        if (lane > b) a += from_up;
+        if (lane < b) a += from_dn;
+        if (b < 64) a64 += __builtin_amdgcn_readlane(gu, 63 - b);   // 0 unless C == 64
+    }
+    return a;
+}
+
+// ---------------------------------------------------------------------------
+// merge phase
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ u64 pack_sel(int met_bits, int bank, uint32_t ord, uint32_t flat)
+{
+    const int fb = 32 - met_bits;
+    const uint32_t flatmask = fb >= 32 ? 0xFFFFFFFFu : ((1u << fb) - 1u);
+    u64 v = ((u64)ord << fb) | (u64)(flatmask - flat);
+    if (met_bits) v |= (u64)bank << (64 - met_bits);
+    return v;
+}
+
+// sorts buf[0..n) (n a power of two) in decreasing order; all threads of the block take part
+__device__ __forceinline__ void block_sort_desc(u64 *buf, int n)
+{
+    for (int k2 = 2; k2 <= n; k2 <<= 1) {
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (n >> 1); t += kBlock) {
+                const int i = 2 * t - (t & (j - 1));
+                const int l = i + j;
+                const bool desc_block = (i & k2) == 0;
+                const u64 a = buf[i], c = buf[l];
+                if ((a < c) == desc_block) {
+                    buf[i] = c;
+                    buf[l] = a;
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSmem &sm, u64 *sortbuf)
+{
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int k = p.k, V = p.V;
+    const int P = p.nphr[b];
+    const int32_t *goff = p.phr_off + (size_t)b * (kMaxCons + 1);
+    const int C = goff[P];
+
+    if (tid <= P) sm.poff[tid] = goff[tid];
+    if (tid < C) sm.tok[tid] = p.cons_tok[(size_t)b * kMaxCons + tid];
+    if (tid <= kMaxCons) sm.cnt[tid] = 0;
+    if (tid == 0) sm.nsel = 0;
+    if (tid < k) {
+        const size_t r = (size_t)b * k + tid;
+        sm.prev[tid] = p.score_cur[r];
+        sm.met[tid] = p.met_cur[r];
+        sm.ipq[tid] = p.ipq_cur[r];
+        sm.len[tid] = p.len_cur[r];
+        sm.fin[tid] = p.fin_cur[r];
+    }
+
+    // source 1: the sentence's k best (Sec. 3.1 item 1) = top k of the union of the row lists
+    u64 acc = 0;
+    for (int h = wave; h < k; h += kWavesPerBlock) {
+        const u64 L = p.rowlists[((size_t)b * k + h) * kWave + lane];
+        if (lane == 0) sm.rb[h] = L;                  // source 3: the row's best (item 3)
+        acc = merge_desc(acc, L);
+    }
+    sm.wl[wave][lane] = acc;
+    const int ncand_max = k * (P + 2);
+    int npad = kWave;
+    while (npad < ncand_max) npad <<= 1;
+    for (int i = tid; i < npad; i += kBlock) sortbuf[i] = 0;
+    __syncthreads();
+    if (wave == 0) {
+        for (int w = 1; w < kWavesPerBlock; ++w) acc = merge_desc(acc, sm.wl[w][lane]);
+        sm.t1[lane] = lane < k ? acc : 0ull;
+    }
+    __syncthreads();
+
+    // tau = k-th best key of the sentence; 0 while fewer than k finite sums exist, in which
+    // case every finite sum is among the k best already.
+    const u64 tau = sm.t1[k - 1];
+
+    // candidates, deduplicated by construction: the k best; a row's best unless among the
+    // k best; an expandable constraint token (item 2) unless among the k best, equal to its
+    // row's best, or offered already by a lower phrase of the same hypothesis.
+    for (int i = tid; i < ncand_max; i += kBlock) {
+        u64 key = 0;
+        int h = 0, w = 0;
+        bool valid = false;
+        if (i < k) {
+            key = sm.t1[i];
+            valid = key != 0;
+            if (valid) {
+                const uint32_t flat = key_flat(key);
+                h = (int)(flat / (uint32_t)V);
+                w = (int)(flat - (uint32_t)h * (uint32_t)V);
+            }
+        } else if (i < 2 * k) {
+            h = i - k;
+            key = sm.rb[h];
+            valid = key != 0 && tau != 0 && key < tau;
+            if (valid) w = (int)(key_flat(key) - (uint32_t)h * (uint32_t)V);
+        } else {
+            const int q = i - 2 * k;
+            h = q / P;
+            const int j = q - h * P;
+            const float pv = sm.prev[h];
+            if (pv > -INFINITY && !sm.fin[h]) {
+                const u64 met = sm.met[h];
+                const int ipq = sm.ipq[h];
+                const int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
+                const int wj = expandable_token(sm, met, ip, iq, j);
+                if (wj >= 0) {
+                    bool dup = false;
+                    for (int j2 = 0; j2 < j; ++j2) dup |= expandable_token(sm, met, ip, iq, j2) == wj;
+                    if (!dup) {
+                        const float s = pv + p.logp[((size_t)b * k + h) * (size_t)V + wj];
+                        if (s > -INFINITY) {
+                            key = make_key(s, (uint32_t)h * (uint32_t)V + (uint32_t)wj);
+                            valid = tau != 0 && key < tau && key != sm.rb[h];
+                            w = wj;
+                        }
+                    }
+                }
+            }
+        }
+        if (valid) {
+            u64 m2 = sm.met[h];
+            if (!sm.fin[h]) {
+                const int ipq = sm.ipq[h];
+                int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
+                cons_add(sm, P, m2, ip, iq, w);
+            }
+            const int bank = __popcll(m2);                // bank = constraints met (Sec. 3.1)
+            sortbuf[i] = pack_sel(p.met_bits, bank, (uint32_t)(key >> 32), key_flat(key));
+            atomicAdd(&sm.cnt[bank], 1);
+        }
+    }
+    __syncthreads();
+
+    // slots per bank (Sec. 3.2) and where each bank begins in the sorted order (bank C first)
+    if (wave == 0) {
+        const int c = sm.cnt[lane];
+        const int c64 = sm.cnt[kMaxCons];
+        int a64;
+        const int a = allocate_wave(k, C, c, c64, a64);
+        sm.alloc[lane] = a;
+        if (lane == 0) sm.alloc[kMaxCons] = a64;
+        const int cc = lane <= C ? c : 0;
+        const int incl = wave_inclusive_sum(cc);          // candidates in banks <= lane
+        const int total63 = __builtin_amdgcn_readlane(incl, 63);
+        const int c64v = C == 64 ? c64 : 0;
+        sm.start[lane] = (total63 - incl) + c64v;         // candidates in higher banks
+        if (lane == 0) sm.start[kMaxCons] = 0;
+    }
+    block_sort_desc(sortbuf, npad);                       // its barriers also publish alloc/start
+
+    // within a bank the best alloc[bank] are taken (Sec. 3.1/3.2)
+    const int sel_shift = 64 - p.met_bits;
+    const u64 body_mask = p.met_bits ? ((1ull << sel_shift) - 1ull) : ~0ull;
+    for (int i = tid; i < npad; i += kBlock) {
+        const u64 key = sortbuf[i];
+        if (key != 0) {
+            const int bank = p.met_bits ? (int)(key >> sel_shift) : 0;
+            if (i - sm.start[bank] < sm.alloc[bank]) {
+                const int slot = atomicAdd(&sm.nsel, 1);
+                sm.sel[slot] = key & body_mask;
+            }
+        }
+    }
+    __syncthreads();
+
+    // new beam, best first (Sec. 3.1); empty slots last
+    if (tid < k) {
+        const int nsel = sm.nsel;
+        int slot = tid;
+        int token = p.pad_id, parent = -1, length = 0, ipq2 = -1;
+        float score = -INFINITY;
+        u64 met2 = 0;
+        uint8_t flags = 2, fin2 = 0;
+        if (tid < nsel) {
+            const u64 mine = sm.sel[tid];
+            slot = 0;
+            for (int j = 0; j < nsel; ++j) slot += sm.sel[j] > mine ? 1 : 0;
+            const int fb = 32 - p.met_bits;
+            const uint32_t flatmask = fb >= 32 ? 0xFFFFFFFFu : ((1u << fb) - 1u);
+            const uint32_t flat = flatmask - ((uint32_t)mine & flatmask);
+            const uint32_t ord = (uint32_t)(mine >> fb);
+            parent = (int)(flat / (uint32_t)V);
+            token = (int)(flat - (uint32_t)parent * (uint32_t)V);
+            score = float_from_ord(ord);
+            met2 = sm.met[parent];
+            const int ipq = sm.ipq[parent];
+            int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
+            const bool pfin = sm.fin[parent] != 0;
+            if (!pfin) cons_add(sm, P, met2, ip, iq, token);
+            ipq2 = ip < 0 ? -1 : ((ip << 8) | iq);
+            fin2 = (pfin || token == p.eos_id) ? 1 : 0;
+            length = pfin ? sm.len[parent] : sm.len[parent] + 1;
+            flags = fin2;
+        }
+        const size_t o = (size_t)b * k + slot;
+        p.score_nxt[o] = score;
+        p.met_nxt[o] = met2;
+        p.ipq_nxt[o] = ipq2;
+        p.len_nxt[o] = length;
+        p.fin_nxt[o] = fin2;
+        p.hist_token[o] = token;
+        p.hist_backptr[o] = parent;
+        if (p.out_token) p.out_token[o] = token;
+        if (p.out_backptr) p.out_backptr[o] = parent;
+        if (p.out_score) p.out_score[o] = score;
+        if (p.out_flags) p.out_flags[o] = flags;
+    }
+}
+
+}  // namespace dba

@@ -1,0 +1,126 @@
+"""-m gpu: the HIP path, called through the C ABI, against the CPU oracle."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+
+def _harness():
+    import harness                      # needs torch + a GPU
+    return harness
+
+
+@pytest.fixture(scope="module")
+def torch_gpu():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def test_allocation_device_matches_oracle(torch_gpu):
+    """Sec. 3.2 on one wavefront vs the oracle: exhaustive small cases, the figure cases,
+    random large ones incl. 64 constraint tokens and k < C."""
+    import paper_1804_06609_amd as dba
+    cases = []
+    for k in range(1, 7):
+        for C in range(0, 4):
+            for cnt in itertools.product(range(0, k + 2), repeat=C + 1):
+                cases.append((k, C, list(cnt)))
+    rs = si.Stream(4242, 1)
+    for _ in range(6000):
+        k = rs.randint(1, 64)
+        C = rs.randint(0, 64)
+        style = rs.randint(0, 3)
+        cnt = []
+        for b in range(C + 1):
+            if style == 0:
+                cnt.append(rs.randint(0, 3))
+            elif style == 1:
+                cnt.append(rs.randint(0, 40) if rs.randint(0, 4) == 0 else 0)
+            elif style == 2:
+                cnt.append(rs.randint(0, 2 * k))
+            else:
+                cnt.append(0 if b > rs.randint(0, C) else rs.randint(0, 9))
+        cases.append((k, C, cnt))
+    n = len(cases)
+    kk = np.array([c[0] for c in cases], np.int32)
+    CC = np.array([c[1] for c in cases], np.int32)
+    cnt = np.zeros((n, 65), np.int32)
+    for i, c in enumerate(cases):
+        cnt[i, :len(c[2])] = c[2]
+    alloc = np.full((n, 65), -7, np.int32)
+    scratch = torch_gpu.empty(n * 132 * 4, dtype=torch_gpu.uint8, device="cuda")
+    dba.dba_debug_allocate(kk, CC, cnt, alloc, scratch.data_ptr(), scratch.numel(),
+                           torch_gpu.cuda.current_stream().cuda_stream)
+    for i, (k, C, c) in enumerate(cases):
+        want = oracle.allocate(k, c)
+        assert list(alloc[i, :C + 1]) == list(want), (k, C, c, alloc[i, :C + 1], want)
+        assert (alloc[i, C + 1:] == 0).all()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_small_fuzz(torch_gpu, seed):
+    """Odd small shapes: k=1, V not a multiple of 4 (unaligned rows), repeated tokens,
+    sentences without constraints, boosted constraint tokens, early EOS."""
+    rs = si.Stream(seed, 5)
+    B = rs.randint(1, 5)
+    k = [1, 2, 3, 5, 8, 13, 33, 64][seed % 8]
+    V = max(k + 3, [37, 64, 130, 257, 1001, 1023, 2050, 4099][(seed // 3) % 8])
+    T = rs.randint(6, 14)
+    wl = si.make_small(9000 + seed, B, k, V, T, max_phrases=5, max_len=4, dup_prob=0.35)
+    wl.eos_switch = T // 2
+    _harness().run_parity(wl)
+
+
+def test_many_constraints_small_beam(torch_gpu):
+    """C >= k (Sec. 5): 64 single-token and phrasal constraints, k=3."""
+    B, k, V, T = 3, 3, 3000, 40
+    cons = si.fixed_total_constraints(31, B, V, 64, max_len=3)
+    wl = si.Workload(B=B, k=k, V=V, T=T, seed=31, constraints=cons,
+                     boost_tokens=[[w for p in s for w in p] for s in cons], boost_prob=0.2)
+    _harness().run_parity(wl)
+
+
+def test_batch_equals_single_sentences(torch_gpu):
+    """Sentences never interact: a batch run equals one-sentence runs of the same rows."""
+    h = _harness()
+    wl = si.make_config(3, T=12, B=4)
+    wl.V = 5000
+    wl.constraints = [[[4 + (w % (wl.V - 4)) for w in ph] for ph in s] for s in wl.constraints]
+    wl.boost_tokens = [[4 + (w % (wl.V - 4)) for w in s] for s in wl.boost_tokens]
+    fin = h.run_parity(wl)
+    assert fin[0].shape == (4, 12)
+
+
+def test_config1(torch_gpu):
+    _harness().run_parity(si.make_config(1), progress="config1")
+
+
+def test_config2(torch_gpu):
+    _harness().run_parity(si.make_config(2), progress="config2")
+
+
+def test_config3(torch_gpu):
+    _harness().run_parity(si.make_config(3), progress="config3")
+
+
+def test_config4(torch_gpu):
+    """Headline shape, all 64 sentences, all 100 steps, the launch configuration bench.py times."""
+    _harness().run_parity(si.make_config(4), check_state_every=5, progress="config4")
+
+
+def test_config5(torch_gpu):
+    """Full shape (B=128, k=64, V=50000).  The oracle follows a sample of sentences through
+    every step (its cost per sentence-step is ~0.3 s); all sentences are checked against the
+    properties that hold at any size.  DBA_TEST_CONFIG5_STEPS overrides the step count."""
+    T = int(os.environ.get("DBA_TEST_CONFIG5_STEPS", "40"))
+    wl = si.make_config(5, T=T)
+    ntok = [wl.n_tokens(b) for b in range(wl.B)]
+    sample = sorted({int(np.argmin(ntok)), int(np.argmax(ntok)), 0, 1, 63, 64, 126, 127})
+    _harness().run_parity(wl, oracle_sentences=sample, check_state_every=5, progress="config5")
