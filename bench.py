@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the DBA step on one MI355X.
+
+python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A "step" is one dba_step call: the whole hot path (score add, top-k, row best, constraint
+gather, state update, banks, allocation, new beam) for one [B,k,V] log-prob tensor that is
+already resident in HBM.  Workload: config 4 (B=64, k=20, V=32000, 32 constraint tokens per
+sentence, decodes of 100 steps).  Steps beyond the 100th start the next decode (contexts are
+initialised before the timed region).  Inputs rotate over several distinct resident tensors so
+that the 164 MB per step cannot be served from the 256 MB Infinity Cache.
+
+Prints ONE JSON line.  `value` = steps/s (wall clock, synchronised on both sides);
+`roofline.achieved` = algorithmic bytes per launch / average launch duration measured with
+HIP events on the launch stream; `cpu_baseline` = the CPU oracle timed on this machine's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+
+def build_workload(cfg: int, cons_tokens):
+    import synth_inputs as si
+    wl = si.make_config(cfg)
+    if cons_tokens is not None:
+        wl.constraints = si.fixed_total_constraints(wl.seed, wl.B, wl.V, cons_tokens)
+    wl.eos_switch = 1 << 30      # every timed row stays live: EOS keeps its low logit
+    return wl
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload (default: the headline config 4)")
+    ap.add_argument("--cons-tokens", type=int, default=None,
+                    help="override: exactly this many constraint tokens per sentence (flatness sweep)")
+    ap.add_argument("--tensors", type=int, default=8, help="distinct resident input tensors to rotate over")
+    ap.add_argument("--decode-len", type=int, default=None, help="steps per decode (default: the config's)")
+    ap.add_argument("--repeats", type=int, default=5, help="timed repetitions; the median is reported")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; sentences shard across GPUs without any "
+              "exchange, so a multi-GPU figure would be N independent copies of this run. "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth_inputs as si
+    from paper_1804_06609_amd.session import Session
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    wl = build_workload(args.config, args.cons_tokens)
+    B, k, V = wl.B, wl.k, wl.V
+    K, W, R = args.steps, args.warmup, max(1, args.tensors)
+    dlen = args.decode_len or wl.T
+    toks, poff, soff = wl.csr()
+
+    # resident inputs
+    host = [wl.logp(t) for t in range(R)]
+    dev = [torch.from_numpy(h).cuda() for h in host]
+    torch.cuda.synchronize()
+
+    def run(nsteps_total):
+        """Fresh contexts, then nsteps_total steps as back-to-back decodes of dlen steps."""
+        n_dec = (nsteps_total + dlen - 1) // dlen
+        return [Session(B, k, V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff) for _ in range(n_dec)]
+
+    stream = torch.cuda.current_stream()
+    wall, evms = [], []
+    for rep in range(args.repeats):
+        sessions = run(W + K)
+        g = 0
+        for _ in range(W):
+            sessions[g // dlen].step(dev[g % R])
+            g += 1
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(K):
+            sessions[g // dlen].step(dev[g % R])
+            g += 1
+        e1.record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        wall.append(t1 - t0)
+        evms.append(e0.elapsed_time(e1))
+        for s in sessions:
+            s.close()
+    wall_s = float(np.median(wall))
+    ev_ms = float(np.median(evms))
+
+    # algorithmic bytes: every live row's V log-probs once.  The first step of a decode has one
+    # live row, all later steps k (EOS never fires in this workload).
+    live_rows = 0
+    for g in range(W, W + K):
+        live_rows += B * (1 if g % dlen == 0 else k)
+    bytes_total = 4.0 * live_rows * V
+    launches = K
+    achieved = bytes_total / launches / (ev_ms * 1e-3 / launches) / 1e9
+
+    ntok = sorted({wl.n_tokens(b) for b in range(B)})
+    ctok_desc = str(ntok[0]) if len(ntok) == 1 else f"{ntok[0]}..{ntok[-1]}"
+    out = {
+        "metric": "DBA steps/sec",
+        "value": K / wall_s,
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": wall_s * 1e3 / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"config{args.config}: B={B} k={k} V={V}, {ctok_desc} constraint tokens/sentence, "
+                        f"decodes of {dlen} steps, {R} rotating resident tensors",
+            "batch": B, "beam": k, "vocab": V, "decode_len": dlen,
+        },
+        "selection_GBps": bytes_total / wall_s / 1e9,
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "kernel": "dba_step_kernel (fused stream+merge, one launch per step)",
+            "us_per_launch": ev_ms * 1e3 / launches,
+            "algorithmic_bytes_per_launch": bytes_total / launches,
+        },
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = min(16, os.cpu_count() or 1)
+        S = 12 if args.config == 4 else 4
+        ob = oracle.BatchBeam(k, V, wl.constraints, wl.eos_id, wl.pad_id)
+        ses = Session(B, k, V, S, wl.eos_id, wl.pad_id, toks, poff, soff)
+        t0 = time.perf_counter()
+        for t in range(S):
+            ob.step(host[t % R], threads=threads)
+        cpu_s = time.perf_counter() - t0
+        same = True
+        for t in range(S):
+            ses.step(dev[t % R])
+        g_tok, g_bp, g_sc, _ = ses.outputs()
+        same = (g_tok.tobytes() == ob.stacked("token").tobytes() and
+                g_bp.tobytes() == ob.stacked("backptr").tobytes() and
+                g_sc.tobytes() == ob.stacked("score").tobytes())
+        ses.close()
+        out["cpu_baseline"] = {
+            "value": S / cpu_s, "unit": "steps/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {S} steps of the same workload, all {B} sentences, one sentence per thread",
+            "gpu_matches_oracle_on_sample": bool(same),
+        }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

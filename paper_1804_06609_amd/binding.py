@@ -32,6 +32,7 @@ _SIGNATURES = {
     "dba_destroy": (None, [_P]),
     "dba_last_error": (ctypes.c_char_p, [_P]),
     "dba_debug_allocate": (_I, [_I] + [_P] * 5 + [ctypes.c_size_t, _P]),
+    "dba_debug_wave_select": (_I, [_I] + [_P] * 5 + [ctypes.c_size_t, _P]),
 }
 
 _lib = None
@@ -129,3 +130,12 @@ def dba_debug_allocate(k: np.ndarray, C: np.ndarray, cnt: np.ndarray, alloc: np.
     return _check(load().dba_debug_allocate(n, _host(k, np.int32), _host(C, np.int32),
                                             _host(cnt, np.int32), _host(alloc, np.int32),
                                             scratch_dev, scratch_bytes, hip_stream or None))
+
+
+def dba_debug_wave_select(keys: np.ndarray, vals: np.ndarray, out: np.ndarray, fout: np.ndarray,
+                          scratch_dev: int, scratch_bytes: int, hip_stream: int = 0) -> int:
+    n = int(keys.shape[0])
+    assert keys.shape == (n, 128) and vals.shape == (n, 64) and out.shape == (n, 192) and fout.shape == (n, 64)
+    return _check(load().dba_debug_wave_select(n, _host(keys, np.uint64), _host(vals, np.float32),
+                                               _host(out, np.uint64), _host(fout, np.float32),
+                                               scratch_dev, scratch_bytes, hip_stream or None))

@@ -16,18 +16,19 @@ using namespace dba;
 // ---------------------------------------------------------------------------
 // kernels
 // ---------------------------------------------------------------------------
-// Grid: one workgroup per beam row.  U = float4 loads each lane keeps in flight per tile.
+// Stream phase.  Grid: one workgroup of blockDim.x/64 waves per beam row.
+// U = float4 loads each lane keeps in flight per tile.
 template <int U>
-__global__ __launch_bounds__(kBlock) void dba_step_kernel(const StepParams p)
+__global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
 {
-    extern __shared__ __align__(16) unsigned char dyn_smem[];
-    __shared__ MergeSmem sm;
+    __shared__ StreamSmem sm;
 
     const int row = blockIdx.x;
     const int b = row / p.k;
     const int h = row - b * p.k;
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
+    const int nwaves = (int)(blockDim.x >> 6);
 
     // the row's hypothesis: wave-uniform by construction, made so for the compiler
     const float prev = __uint_as_float(
@@ -37,7 +38,10 @@ __global__ __launch_bounds__(kBlock) void dba_step_kernel(const StepParams p)
     RowTop st;
     st.list = 0;
     st.kth = 0;
-    st.thr = -INFINITY;
+    st.floor = -INFINITY;
+    st.thr = kLowestFinite;
+    if (threadIdx.x == 0) sm.thr = ord_from_float(-INFINITY);
+    __syncthreads();
     if (prev > -INFINITY && !fin) {
         const int P = p.nphr[b];
         const int C = p.phr_off[(size_t)b * (kMaxCons + 1) + P];
@@ -45,41 +49,52 @@ __global__ __launch_bounds__(kBlock) void dba_step_kernel(const StepParams p)
         // Sec. 3.3: no end-of-sentence before all constraints are met
         const int eos_block = __builtin_amdgcn_readfirstlane(nmet < C ? p.eos_id : -1);
         stream_row<U>(p.logp + (size_t)row * (size_t)p.V, p.V, prev, eos_block,
-                      (uint32_t)h * (uint32_t)p.V, p.k, wave, kWavesPerBlock, st);
+                      (uint32_t)h * (uint32_t)p.V, p.k, wave, nwaves, sm, st);
     } else if (prev > -INFINITY && wave == 0 && lane == 0) {
         // a finished hypothesis stays on the beam: its one continuation is the pad token
         // at log-prob +0.0, score carried unchanged
         st.list = make_key(prev + 0.0f, (uint32_t)h * (uint32_t)p.V + (uint32_t)p.pad_id);
     }
-    sm.wl[wave][lane] = st.list;
-    __syncthreads();
+    if (nwaves > 1) {
+        sm.wl[wave][lane] = st.list;
+        __syncthreads();
+    }
     if (wave == 0) {
         u64 acc = st.list;
-        for (int w = 1; w < kWavesPerBlock; ++w) acc = merge_desc(acc, sm.wl[w][lane]);
+        for (int w = 1; w < nwaves; ++w) acc = merge_desc(acc, sm.wl[w][lane]);
         p.rowlists[(size_t)row * kWave + lane] = acc;
     }
-    if (!p.fused) return;
-
-    // Last workgroup of the sentence to deliver its list runs the merge phase.
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int old = atomicAdd(&p.counters[b], 1u);
-        sm.last = (old == (unsigned int)(p.k - 1)) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!sm.last) return;
-    __threadfence();
-    if (threadIdx.x == 0) p.counters[b] = 0;
-    merge_phase(p, b, sm, reinterpret_cast<u64 *>(dyn_smem));
 }
 
-// Grid: one workgroup per sentence (the two-launch form of the step).
+// Merge phase.  Grid: one workgroup per sentence.
 __global__ __launch_bounds__(kBlock) void dba_merge_kernel(const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ MergeSmem sm;
     merge_phase(p, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
+}
+
+// Diagnostic: the wavefront selection primitives on caller-provided keys, one wave per case.
+// in: keys[128] per case, vals[64] per case.  out[0:64] = sort of keys[0:64];
+// out[64:128] = merge of sort(keys[0:64]) and sort(keys[64:128]); out[128:192] = the first
+// list after inserting keys[64..71] one at a time; fout[0:64] = sort of vals.
+__global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float *vals, u64 *out,
+                                       float *fout)
+{
+    const int i = blockIdx.x;
+    if (i >= n_cases) return;
+    const int lane = lane_id();
+    const u64 a = sort64_desc(keys[(size_t)i * 128 + lane]);
+    const u64 b = sort64_desc(keys[(size_t)i * 128 + 64 + lane]);
+    out[(size_t)i * 192 + lane] = a;
+    out[(size_t)i * 192 + 64 + lane] = merge_desc(a, b);
+    u64 l = a;
+    for (int j = 0; j < 8; ++j) {
+        const u64 x = keys[(size_t)i * 128 + 64 + j];
+        l = insert_desc(l, x);
+    }
+    out[(size_t)i * 192 + 128 + lane] = l;
+    fout[(size_t)i * 64 + lane] = sort64_desc_f32(vals[(size_t)i * 64 + lane]);
 }
 
 // decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0
@@ -228,6 +243,7 @@ struct dba_ctx {
     int steps;
     int fused;
     int unroll;
+    int waves;
     size_t dyn_smem;
     unsigned char *ws;
     Layout L;
@@ -348,8 +364,10 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->ws = static_cast<unsigned char *>(workspace_dev);
     c->L = L;
     c->stream = static_cast<hipStream_t>(hip_stream);
-    c->fused = env_int("DBA_FUSED", 1) ? 1 : 0;
+    c->fused = 0;
     c->unroll = env_int("DBA_UNROLL", 4);
+    c->waves = env_int("DBA_WAVES", 4);
+    if (c->waves != 1 && c->waves != 2 && c->waves != 4) c->waves = 4;
     int npad = kWave;
     while (npad < k * (max_phrases + 2)) npad <<= 1;
     c->dyn_smem = (size_t)npad * sizeof(u64);
@@ -417,14 +435,13 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.hist_token = at<int32_t>(c, L.hist_token) + hrow;
     p.hist_backptr = at<int32_t>(c, L.hist_backptr) + hrow;
 
-    const dim3 grid((unsigned)(c->B * c->k)), block(kBlock);
-    const size_t smem = c->fused ? c->dyn_smem : 0;
+    const dim3 grid((unsigned)(c->B * c->k)), block((unsigned)(c->waves * kWave));
     switch (c->unroll) {
-        case 2: dba_step_kernel<2><<<grid, block, smem, c->stream>>>(p); break;
-        case 8: dba_step_kernel<8><<<grid, block, smem, c->stream>>>(p); break;
-        default: dba_step_kernel<4><<<grid, block, smem, c->stream>>>(p); break;
+        case 2: dba_stream_kernel<2><<<grid, block, 0, c->stream>>>(p); break;
+        case 8: dba_stream_kernel<8><<<grid, block, 0, c->stream>>>(p); break;
+        default: dba_stream_kernel<4><<<grid, block, 0, c->stream>>>(p); break;
     }
-    if (!c->fused) dba_merge_kernel<<<dim3((unsigned)c->B), block, c->dyn_smem, c->stream>>>(p);
+    dba_merge_kernel<<<dim3((unsigned)c->B), dim3(kBlock), c->dyn_smem, c->stream>>>(p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_step: launch failed: %s", hipGetErrorString(e));
     c->steps += 1;
@@ -521,6 +538,33 @@ DBA_API int dba_debug_allocate(int n_cases, const int32_t *k_host, const int32_t
     if (e == hipSuccess) e = hipMemcpyAsync(alloc_host, d_alloc, n * 65 * 4, hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return fail(nullptr, DBA_EHIP, "dba_debug_allocate: HIP error: %s", hipGetErrorString(e));
+    return DBA_OK;
+}
+
+DBA_API int dba_debug_wave_select(int n_cases, const uint64_t *keys_host, const float *vals_host,
+                                  uint64_t *out_host, float *fout_host, void *scratch_dev,
+                                  size_t scratch_bytes, void *hip_stream)
+{
+    if (n_cases < 1 || !keys_host || !vals_host || !out_host || !fout_host || !scratch_dev)
+        return fail(nullptr, DBA_EINVAL, "dba_debug_wave_select: bad argument");
+    const size_t n = (size_t)n_cases;
+    if (scratch_bytes < n * (128 * 8 + 192 * 8 + 64 * 4 + 64 * 4))
+        return fail(nullptr, DBA_ENOMEM, "dba_debug_wave_select: scratch too small");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    u64 *d_keys = static_cast<u64 *>(scratch_dev);
+    u64 *d_out = d_keys + n * 128;
+    float *d_vals = reinterpret_cast<float *>(d_out + n * 192);
+    float *d_fout = d_vals + n * 64;
+    hipError_t e = hipMemcpyAsync(d_keys, keys_host, n * 128 * 8, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(d_vals, vals_host, n * 64 * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) {
+        dba_wave_select_kernel<<<dim3((unsigned)n_cases), dim3(kWave), 0, s>>>(n_cases, d_keys, d_vals, d_out, d_fout);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpyAsync(out_host, d_out, n * 192 * 8, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(fout_host, d_fout, n * 64 * 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(nullptr, DBA_EHIP, "dba_debug_wave_select: HIP error: %s", hipGetErrorString(e));
     return DBA_OK;
 }
 

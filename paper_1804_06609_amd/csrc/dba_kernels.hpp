@@ -83,28 +83,45 @@ struct MergeSmem {
 struct RowTop {
     u64 list;      // this lane's entry of the wave's decreasing top-64
     u64 kth;       // key at place k-1 (0 while fewer than k entries)
-    float thr;     // score of kth, -inf while fewer than k entries
+    float floor;   // a proven lower bound of the row's k-th best sum (-inf if none)
+    float thr;     // sums below this cannot reach the row's top k; never below -FLT_MAX, so
+                   // that "s >= thr" also rejects -inf sums
 };
+
+constexpr float kLowestFinite = -3.402823466e+38f;
 
 __device__ __forceinline__ void refresh_threshold(RowTop &st, int kk)
 {
     st.kth = read_lane(st.list, kk - 1);
-    st.thr = (st.kth == 0) ? -INFINITY : float_from_ord((uint32_t)(st.kth >> 32));
+    const float own = (st.kth == 0) ? kLowestFinite : float_from_ord((uint32_t)(st.kth >> 32));
+    st.thr = fmaxf(fmaxf(st.floor, own), kLowestFinite);
 }
 
-// Wave-wide: every lane offers at most one element (pass = it may belong to the top k).
-__device__ __forceinline__ void consider(RowTop &st, float s, uint32_t flat, bool pass, int kk)
+// Key of a wave-uniform element, built from uniform values (scalar unit).
+__device__ __forceinline__ u64 make_key_uniform(uint32_t sbits, uint32_t flat)
 {
-    u64 m = __ballot(pass);
-    if (m == 0) return;
-    const u64 key = pass ? make_key(s, flat) : 0ull;
+    if (sbits == 0x80000000u) sbits = 0;                       // -0.0 -> +0.0
+    const uint32_t mask = (uint32_t)((int32_t)sbits >> 31);    // all ones for negative floats
+    const uint32_t ord = sbits ^ (mask | 0x80000000u);
+    return ((u64)ord << 32) | (u64)(0xFFFFFFFFu - flat);
+}
+
+// Wave-wide: every lane offers one element; m = ballot of the lanes whose sum may belong to
+// the top k.  flat0 = coordinate of lane 0's element, lane l holds flat0 + l*lane_stride.
+__device__ __forceinline__ void consider(RowTop &st, float s, u64 m, uint32_t flat0,
+                                         uint32_t lane_stride, int kk)
+{
     if (__popcll(m) > kSortThresh) {
+        const int lane = lane_id();
+        const bool pass = (m >> lane) & 1ull;
+        const u64 key = pass ? make_key(s, flat0 + (uint32_t)lane * lane_stride) : 0ull;
         st.list = merge_desc(st.list, sort64_desc(key));
     } else {
         do {
             const int l = __ffsll((long long)m) - 1;
             m &= m - 1;
-            const u64 x = read_lane(key, l);
+            const uint32_t sbits = (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(s), l);
+            const u64 x = make_key_uniform(sbits, flat0 + (uint32_t)l * lane_stride);
             if (x > st.kth) {
                 st.list = insert_desc(st.list, x);
                 st.kth = read_lane(st.list, kk - 1);
@@ -114,37 +131,81 @@ __device__ __forceinline__ void consider(RowTop &st, float s, uint32_t flat, boo
     refresh_threshold(st, kk);
 }
 
-__device__ __forceinline__ float4 neg_inf4()
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ v4f neg_inf4()
 {
-    return make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    return v4f{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 }
 
+__device__ __forceinline__ float max4(const v4f &x)
+{
+    return fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+}
+
+// The log-probs are read exactly once: non-temporal loads keep them from displacing
+// anything useful in the caches.
 template <int U>
-__device__ __forceinline__ void load_tile(const float4 *__restrict__ vec, int nv, int tile, int lane,
-                                          float4 (&x)[U])
+__device__ __forceinline__ void load_tile(const v4f *__restrict__ vec, int nv, int tile, int lane,
+                                          v4f (&x)[U])
 {
     const int base = tile * (kWave * U);
     if (base + kWave * U <= nv) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) x[u] = vec[base + u * kWave + lane];
+        for (int u = 0; u < U; ++u) x[u] = __builtin_nontemporal_load(vec + base + u * kWave + lane);
     } else {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = base + u * kWave + lane;
-            x[u] = (i < nv) ? vec[i] : neg_inf4();
+            x[u] = (i < nv) ? __builtin_nontemporal_load(vec + i) : neg_inf4();
         }
     }
 }
 
-// One wave's share of one row.  s = prev + logp is a single fp32 add; an element
-// is looked at closely only if its sum can still reach the wave's current k-th
-// best (>=: a later element may tie the k-th score and win on the coordinate).
-// Because rounding is monotone, max(prev + x_i) == prev + max(x_i), so one add
-// per float4 suffices for the test.
+// Sec. 3.3: while constraints are unmet the end-of-sentence entry does not exist.  rel = its
+// position inside the tile in floats (wave-uniform); the one lane holding it drops it.
+template <int U>
+__device__ __forceinline__ void block_eos(v4f (&x)[U], int rel, int lane)
+{
+    const int uu = rel / (4 * kWave), ln = (rel >> 2) & (kWave - 1), c = rel & 3;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (u == uu && lane == ln) {
+            if (c == 0) x[u].x = -INFINITY;
+            if (c == 1) x[u].y = -INFINITY;
+            if (c == 2) x[u].z = -INFINITY;
+            if (c == 3) x[u].w = -INFINITY;
+        }
+    }
+}
+
+// LDS shared by the waves of one row's workgroup during the stream phase.
+struct StreamSmem {
+    u64 wl[kWavesPerBlock][kWave];      // the waves' lists, for the final merge
+    float boot[kWavesPerBlock][kWave];  // sorted per-lane maxima of every wave's first tile
+    unsigned int thr;                   // best bound any wave has published (order-preserving u32)
+};
+
+// One wave's share of one row: tiles wave, wave+nwaves, ... of 64*U float4 each.  Must be
+// called by every thread of the workgroup (it contains one barrier).
+//
+// s = prev + logp is a single fp32 add.  An element is looked at closely only if its sum can
+// still reach the row's k best (>=: a later element may tie the k-th score and win on the
+// coordinate).  Rounding is monotone, so max(prev + x_i) == prev + max(x_i): one add per
+// float4 decides whether any of its four elements needs a look.
+//
+// Thresholds.  (1) Every lane takes the maximum of its share of the wave's first tile; the
+// k-th greatest of all the workgroup's per-lane maxima is a floor: k different lanes hold an
+// element at least that large, so nothing below it can be among the row's k best.  (2) A wave
+// whose own list holds k entries uses the score of its k-th, publishes it into sm.thr (atomic
+// max on an order-preserving u32) and re-reads the workgroup's maximum once per tile.  Any
+// wave's bound holds for the whole row, so a stale value only lets a few more elements
+// through; it never drops one.  The row's best element is never below any bound, so it
+// always survives.
 template <int U>
 __device__ __forceinline__ void stream_row(const float *__restrict__ row, int V, float prev,
                                            int eos_block, uint32_t flat_base, int kk, int wave,
-                                           int nwaves, RowTop &st)
+                                           int nwaves, StreamSmem &sm, RowTop &st)
 {
     const int lane = lane_id();
     const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
@@ -152,44 +213,83 @@ __device__ __forceinline__ void stream_row(const float *__restrict__ row, int V,
     if (head > V) head = V;
     const int nv = (V - head) >> 2;
     const int tail = V - head - (nv << 2);
-    const float4 *__restrict__ vec = reinterpret_cast<const float4 *>(row + head);
+    const v4f *__restrict__ vec = reinterpret_cast<const v4f *>(row + head);
     const int ntiles = (nv + kWave * U - 1) / (kWave * U);
+    const int eos_rel0 = eos_block >= 0 ? eos_block - head : -1;   // position in the aligned body
 
-    float4 cur[U], nxt[U];
+    v4f cur[U], nxt[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) nxt[u] = neg_inf4();
     int tl = wave;
-    if (tl < ntiles) load_tile<U>(vec, nv, tl, lane, cur);
+    float boot = -INFINITY;
+    if (tl < ntiles) {
+        load_tile<U>(vec, nv, tl, lane, cur);
+        if (nwaves + tl < ntiles) load_tile<U>(vec, nv, tl + nwaves, lane, nxt);
+        const int rel = eos_rel0 - tl * (4 * kWave * U);
+        if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(cur, rel, lane);
+        float lane_max = max4(cur[0]);
+#pragma unroll
+        for (int u = 1; u < U; ++u) lane_max = fmaxf(lane_max, max4(cur[u]));
+        boot = sort64_desc_f32(prev + lane_max);
+    }
+    if (nwaves > 1) {
+        sm.boot[wave][lane] = boot;
+        __syncthreads();
+        for (int w = 0; w < nwaves; ++w)
+            if (w != wave) boot = merge_desc_f32(boot, sm.boot[w][lane]);
+    }
+    st.floor = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(boot), kk - 1));
+    st.thr = fmaxf(st.floor, kLowestFinite);
     while (tl < ntiles) {
         const int nx = tl + nwaves;
-        if (nx < ntiles) load_tile<U>(vec, nv, nx, lane, nxt);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const float4 x = cur[u];
-            const float m4 = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
-            if (__any(prev + m4 >= st.thr)) {
-                const int w0 = head + 4 * ((tl * U + u) * kWave + lane);
-                const float xs[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const float s = prev + xs[c];
-                    const bool pass = (s >= st.thr) && (s > -INFINITY) && (w0 + c != eos_block);
-                    consider(st, s, flat_base + (uint32_t)(w0 + c), pass, kk);
-                }
+            const v4f x = cur[u];
+            if (__any(prev + max4(x) >= st.thr)) {
+                const uint32_t flat0 = flat_base + (uint32_t)(head + 4 * ((tl * U + u) * kWave));
+                const float s0 = prev + x.x, s1 = prev + x.y, s2 = prev + x.z, s3 = prev + x.w;
+                const u64 m0 = __ballot(s0 >= st.thr);
+                if (m0) consider(st, s0, m0, flat0, 4u, kk);
+                const u64 m1 = __ballot(s1 >= st.thr);
+                if (m1) consider(st, s1, m1, flat0 + 1u, 4u, kk);
+                const u64 m2 = __ballot(s2 >= st.thr);
+                if (m2) consider(st, s2, m2, flat0 + 2u, 4u, kk);
+                const u64 m3 = __ballot(s3 >= st.thr);
+                if (m3) consider(st, s3, m3, flat0 + 3u, 4u, kk);
+                if (nwaves > 1 && lane == 0 && st.kth != 0) atomicMax(&sm.thr, ord_from_float(st.thr));
             }
         }
+        if (nx < ntiles) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+            for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+            if (nx + nwaves < ntiles) load_tile<U>(vec, nv, nx + nwaves, lane, nxt);
+            const int rel = eos_rel0 - nx * (4 * kWave * U);
+            if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(cur, rel, lane);
+            if (nwaves > 1) {
+                st.floor = fmaxf(st.floor, float_from_ord(sm.thr));
+                st.thr = fmaxf(st.thr, st.floor);
+            }
+        }
         tl = nx;
     }
     // elements before the first / after the last 16-byte aligned group (rows whose
-    // length or start is not a multiple of four floats)
+    // length or start is not a multiple of four floats): at most 3 + 3, one per lane
     if (wave == 0 && head + tail > 0) {
         const bool mine = lane < head + tail;
         const int w = lane < head ? lane : head + (nv << 2) + (lane - head);
         const float s = mine ? prev + row[w] : -INFINITY;
-        const bool pass = mine && (s >= st.thr) && (s > -INFINITY) && (w != eos_block);
-        consider(st, s, flat_base + (uint32_t)w, pass, kk);
+        u64 m = __ballot(mine && (s >= st.thr) && (w != eos_block));
+        while (m) {
+            const int l = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const int wl = l < head ? l : head + (nv << 2) + (l - head);
+            const uint32_t sbits = (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(s), l);
+            const u64 x = make_key_uniform(sbits, flat_base + (uint32_t)wl);
+            if (x > st.kth) {
+                st.list = insert_desc(st.list, x);
+                refresh_threshold(st, kk);
+            }
+        }
     }
 }
 

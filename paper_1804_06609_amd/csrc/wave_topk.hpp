@@ -1,10 +1,14 @@
-// Wavefront-level selection primitives for gfx950 (64 lanes).
+// Wavefront-level selection primitives for gfx950 (64 lanes), registers only.
 //
 // A "list" is 64 keys, one per lane, sorted in decreasing order; unused places
 // hold 0.  Keys are 64-bit and strictly ordered: the high word is an
 // order-preserving image of an fp32 score, the low word is the complement of
 // the flat coordinate h*V+w, so "greater key" means "higher score, then lower
 // coordinate" - the tie rule of the step - and no two live keys are equal.
+//
+// Lane exchanges use DPP (quad permutes, row mirrors, wave shift) inside a row
+// of 16 lanes and the gfx950 permlane16/32 swaps across rows, so a compare-
+// exchange stage costs a handful of VALU instructions and never touches LDS.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -50,46 +54,175 @@ __device__ __forceinline__ u64 read_lane(u64 v, int l)
 __device__ __forceinline__ u64 umax64(u64 a, u64 b) { return a > b ? a : b; }
 __device__ __forceinline__ u64 umin64(u64 a, u64 b) { return a < b ? a : b; }
 
-// Full bitonic sort of one key per lane, decreasing by lane.
+// ---- lane permutations of one 32-bit register ------------------------------
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppQuadRev = 0x1B;     // quad_perm [3,2,1,0]   lane ^ 3
+constexpr int kDppWaveShr1 = 0x138;   // lane i reads lane i-1 (lane 0 reads 0)
+constexpr int kDppRowMirror = 0x140;  // lane ^ 15
+constexpr int kDppHalfMirror = 0x141; // lane ^ 7
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+
+// value held by lane (lane ^ 16): rows of 16 lanes are exchanged pairwise
+__device__ __forceinline__ uint32_t xor16_u32(uint32_t v)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return (lane_id() & 16) ? r[0] : r[1];
+}
+
+// value held by lane (lane ^ 32): the wave's halves are exchanged
+__device__ __forceinline__ uint32_t xor32_u32(uint32_t v)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return (lane_id() & 32) ? r[0] : r[1];
+}
+
+// value held by lane (lane ^ J), J a power of two
+template <int J>
+__device__ __forceinline__ uint32_t xor_lane_u32(uint32_t v)
+{
+    if constexpr (J == 1) return dpp_mov<kDppXor1>(v);
+    else if constexpr (J == 2) return dpp_mov<kDppXor2>(v);
+    else if constexpr (J == 4) return dpp_mov<kDppQuadRev>(dpp_mov<kDppHalfMirror>(v));
+    else if constexpr (J == 8) return dpp_mov<kDppHalfMirror>(dpp_mov<kDppRowMirror>(v));
+    else if constexpr (J == 16) return xor16_u32(v);
+    else return xor32_u32(v);
+}
+
+// value held by the mirror lane inside blocks of S lanes: lane ^ (S-1)
+template <int S>
+__device__ __forceinline__ uint32_t flip_lane_u32(uint32_t v)
+{
+    if constexpr (S == 2) return dpp_mov<kDppXor1>(v);
+    else if constexpr (S == 4) return dpp_mov<kDppQuadRev>(v);
+    else if constexpr (S == 8) return dpp_mov<kDppHalfMirror>(v);
+    else if constexpr (S == 16) return dpp_mov<kDppRowMirror>(v);
+    else if constexpr (S == 32) return dpp_mov<kDppRowMirror>(xor16_u32(v));
+    else return dpp_mov<kDppRowMirror>(xor16_u32(xor32_u32(v)));
+}
+
+template <int J>
+__device__ __forceinline__ u64 xor_lane(u64 v)
+{
+    return ((u64)xor_lane_u32<J>((uint32_t)(v >> 32)) << 32) | xor_lane_u32<J>((uint32_t)v);
+}
+
+template <int S>
+__device__ __forceinline__ u64 flip_lane(u64 v)
+{
+    return ((u64)flip_lane_u32<S>((uint32_t)(v >> 32)) << 32) | flip_lane_u32<S>((uint32_t)v);
+}
+
+// ---- compare-exchange networks ------------------------------------------------
+// half-cleaner at distance J: the lower lane of each pair keeps the greater key
+template <int J>
+__device__ __forceinline__ u64 clean_desc(u64 key)
+{
+    const u64 other = xor_lane<J>(key);
+    return ((lane_id() & J) == 0) ? umax64(key, other) : umin64(key, other);
+}
+
+// sorts a bitonic run inside every block of S lanes, decreasing
+template <int S>
+__device__ __forceinline__ u64 bitonic_finish_desc(u64 key)
+{
+    if constexpr (S >= 64) key = clean_desc<32>(key);
+    if constexpr (S >= 32) key = clean_desc<16>(key);
+    if constexpr (S >= 16) key = clean_desc<8>(key);
+    if constexpr (S >= 8) key = clean_desc<4>(key);
+    if constexpr (S >= 4) key = clean_desc<2>(key);
+    if constexpr (S >= 2) key = clean_desc<1>(key);
+    return key;
+}
+
+// merges the two decreasing halves of every block of S lanes into one decreasing block
+template <int S>
+__device__ __forceinline__ u64 merge_halves_desc(u64 key)
+{
+    const u64 other = flip_lane<S>(key);
+    key = ((lane_id() & (S >> 1)) == 0) ? umax64(key, other) : umin64(key, other);
+    return bitonic_finish_desc<(S >> 1)>(key);
+}
+
+// Full sort of one key per lane, decreasing by lane.
 __device__ __forceinline__ u64 sort64_desc(u64 key)
 {
-    const int lane = lane_id();
-#pragma unroll
-    for (int k2 = 2; k2 <= kWave; k2 <<= 1) {
-#pragma unroll
-        for (int j = k2 >> 1; j > 0; j >>= 1) {
-            const u64 other = __shfl_xor(key, j, kWave);
-            const bool desc_block = (lane & k2) == 0;   // k2 == 64: every lane
-            const bool lower = (lane & j) == 0;
-            key = (lower == desc_block) ? umax64(key, other) : umin64(key, other);
-        }
-    }
+    key = merge_halves_desc<2>(key);
+    key = merge_halves_desc<4>(key);
+    key = merge_halves_desc<8>(key);
+    key = merge_halves_desc<16>(key);
+    key = merge_halves_desc<32>(key);
+    key = merge_halves_desc<64>(key);
     return key;
 }
 
 // a, b: decreasing lists.  Returns the 64 greatest of their union, decreasing.
 __device__ __forceinline__ u64 merge_desc(u64 a, u64 b)
 {
-    const int lane = lane_id();
-    const u64 b_rev = __shfl(b, kWave - 1 - lane, kWave);
-    u64 c = umax64(a, b_rev);                           // bitonic, holds the top 64
-#pragma unroll
-    for (int j = kWave >> 1; j > 0; j >>= 1) {
-        const u64 other = __shfl_xor(c, j, kWave);
-        c = ((lane & j) == 0) ? umax64(c, other) : umin64(c, other);
-    }
-    return c;
+    const u64 c = umax64(a, flip_lane<64>(b));          // bitonic, holds the top 64
+    return bitonic_finish_desc<64>(c);
 }
 
 // Insert the wave-uniform key x (x != 0, not already present) into a decreasing list;
 // the smallest entry falls off the end.
 __device__ __forceinline__ u64 insert_desc(u64 list, u64 x)
 {
-    const int lane = lane_id();
-    const u64 up = __shfl_up(list, 1, kWave);
+    const u64 up = ((u64)dpp_mov<kDppWaveShr1>((uint32_t)(list >> 32)) << 32) |
+                   dpp_mov<kDppWaveShr1>((uint32_t)list);
     const bool keep = list > x;
-    const bool prev_keeps = (lane == 0) || (up > x);
+    const bool prev_keeps = (lane_id() == 0) || (up > x);
     return keep ? list : (prev_keeps ? x : up);
+}
+
+// ---- the same network on fp32 values (no NaNs) --------------------------------
+template <int J>
+__device__ __forceinline__ float clean_desc_f32(float v)
+{
+    const float other = __uint_as_float(xor_lane_u32<J>(__float_as_uint(v)));
+    return ((lane_id() & J) == 0) ? fmaxf(v, other) : fminf(v, other);
+}
+
+template <int S>
+__device__ __forceinline__ float bitonic_finish_desc_f32(float v)
+{
+    if constexpr (S >= 64) v = clean_desc_f32<32>(v);
+    if constexpr (S >= 32) v = clean_desc_f32<16>(v);
+    if constexpr (S >= 16) v = clean_desc_f32<8>(v);
+    if constexpr (S >= 8) v = clean_desc_f32<4>(v);
+    if constexpr (S >= 4) v = clean_desc_f32<2>(v);
+    if constexpr (S >= 2) v = clean_desc_f32<1>(v);
+    return v;
+}
+
+template <int S>
+__device__ __forceinline__ float merge_halves_desc_f32(float v)
+{
+    const float other = __uint_as_float(flip_lane_u32<S>(__float_as_uint(v)));
+    v = ((lane_id() & (S >> 1)) == 0) ? fmaxf(v, other) : fminf(v, other);
+    return bitonic_finish_desc_f32<(S >> 1)>(v);
+}
+
+__device__ __forceinline__ float sort64_desc_f32(float v)
+{
+    v = merge_halves_desc_f32<2>(v);
+    v = merge_halves_desc_f32<4>(v);
+    v = merge_halves_desc_f32<8>(v);
+    v = merge_halves_desc_f32<16>(v);
+    v = merge_halves_desc_f32<32>(v);
+    v = merge_halves_desc_f32<64>(v);
+    return v;
+}
+
+// a, b: decreasing.  The 64 greatest of their union, decreasing.
+__device__ __forceinline__ float merge_desc_f32(float a, float b)
+{
+    const float b_rev = __uint_as_float(flip_lane_u32<64>(__float_as_uint(b)));
+    return bitonic_finish_desc_f32<64>(fmaxf(a, b_rev));
 }
 
 // Inclusive prefix sum over the lanes.

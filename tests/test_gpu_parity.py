@@ -64,6 +64,37 @@ def test_allocation_device_matches_oracle(torch_gpu):
         assert (alloc[i, C + 1:] == 0).all()
 
 
+def test_wave_selection_primitives(torch_gpu):
+    """The 64-lane sort / merge / insert networks (DPP and permlane exchanges) against a host
+    sort, on random distinct keys, keys differing only in the low word, and sentinels."""
+    import paper_1804_06609_amd as dba
+    n = 512
+    rng = np.random.default_rng(7)
+    keys = rng.integers(1, 2 ** 63, size=(n, 128), dtype=np.int64).astype(np.uint64)
+    keys[1::4] = (keys[1::4] & np.uint64(0xFFFF)) | (np.uint64(0x3F800000) << np.uint64(32)) | \
+        (np.arange(128, dtype=np.uint64)[None, :] << np.uint64(16))      # equal high words
+    keys[2::4, 40:64] = 0                                                  # short first list
+    keys[2::4, 100:] = 0                                                   # short second list
+    keys[3::4, :64] = 0                                                    # empty first list
+    vals = rng.standard_normal((n, 64)).astype(np.float32) * 10
+    vals[5::8, 10:30] = -np.inf
+    vals[6::8, :] = np.float32(-3.25)
+    out = np.zeros((n, 192), np.uint64)
+    fout = np.zeros((n, 64), np.float32)
+    scratch = torch_gpu.empty(n * 3072, dtype=torch_gpu.uint8, device="cuda")
+    dba.dba_debug_wave_select(keys, vals, out, fout, scratch.data_ptr(), scratch.numel(),
+                              torch_gpu.cuda.current_stream().cuda_stream)
+    for i in range(n):
+        a = np.sort(keys[i, :64])[::-1]
+        assert (out[i, :64] == a).all(), i
+        both = np.sort(keys[i])[::-1][:64]
+        assert (out[i, 64:128] == both).all(), i
+        ins = np.sort(np.concatenate([keys[i, :64], keys[i, 64:72][keys[i, 64:72] != 0]]))[::-1][:64]
+        if (keys[i, 64:72] != 0).all():
+            assert (out[i, 128:192] == ins).all(), i
+        assert fout[i].tobytes() == np.sort(vals[i])[::-1].tobytes(), i
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_small_fuzz(torch_gpu, seed):
     """Odd small shapes: k=1, V not a multiple of 4 (unaligned rows), repeated tokens,
