@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
     }
     if (wave == 0) {
         u64 acc = st.list;
-        for (int w = 1; w < nwaves; ++w) acc = merge_desc(acc, sm.wl[w][lane]);
+        for (int w = 1; w < nwaves; ++w) acc = merge_desc<u64>(acc, sm.wl[w][lane]);
         p.rowlists[(size_t)row * kWave + lane] = acc;
     }
 }
@@ -84,17 +84,17 @@ __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float
     const int i = blockIdx.x;
     if (i >= n_cases) return;
     const int lane = lane_id();
-    const u64 a = sort64_desc(keys[(size_t)i * 128 + lane]);
-    const u64 b = sort64_desc(keys[(size_t)i * 128 + 64 + lane]);
+    const u64 a = sort64_desc<u64>(keys[(size_t)i * 128 + lane]);
+    const u64 b = sort64_desc<u64>(keys[(size_t)i * 128 + 64 + lane]);
     out[(size_t)i * 192 + lane] = a;
-    out[(size_t)i * 192 + 64 + lane] = merge_desc(a, b);
+    out[(size_t)i * 192 + 64 + lane] = merge_desc<u64>(a, b);
     u64 l = a;
     for (int j = 0; j < 8; ++j) {
         const u64 x = keys[(size_t)i * 128 + 64 + j];
         l = insert_desc(l, x);
     }
     out[(size_t)i * 192 + 128 + lane] = l;
-    fout[(size_t)i * 64 + lane] = sort64_desc_f32(vals[(size_t)i * 64 + lane]);
+    fout[(size_t)i * 64 + lane] = float_from_ord(sort64_desc<uint32_t>(ord_from_float(vals[(size_t)i * 64 + lane])));
 }
 
 // decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0

@@ -106,29 +106,40 @@ __device__ __forceinline__ u64 make_key_uniform(uint32_t sbits, uint32_t flat)
     return ((u64)ord << 32) | (u64)(0xFFFFFFFFu - flat);
 }
 
-// Wave-wide: every lane offers one element; m = ballot of the lanes whose sum may belong to
-// the top k.  flat0 = coordinate of lane 0's element, lane l holds flat0 + l*lane_stride.
-__device__ __forceinline__ void consider(RowTop &st, float s, u64 m, uint32_t flat0,
-                                         uint32_t lane_stride, int kk)
+constexpr int kStageCap = 128;        // candidate keys one wave can park in LDS between flushes
+
+// Candidates of one wave are parked in LDS (stage[0..cnt)) and folded into the wave's sorted
+// list 64 at a time: one 64-lane sort and one merge per chunk instead of one serial insert per
+// candidate.  The threshold tightens at every flush.
+__device__ __attribute__((noinline)) u64 fold_stage(u64 list, const u64 *stage, int cnt)
 {
-    if (__popcll(m) > kSortThresh) {
-        const int lane = lane_id();
-        const bool pass = (m >> lane) & 1ull;
-        const u64 key = pass ? make_key(s, flat0 + (uint32_t)lane * lane_stride) : 0ull;
-        st.list = merge_desc(st.list, sort64_desc(key));
-    } else {
-        do {
-            const int l = __ffsll((long long)m) - 1;
-            m &= m - 1;
-            const uint32_t sbits = (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(s), l);
-            const u64 x = make_key_uniform(sbits, flat0 + (uint32_t)l * lane_stride);
-            if (x > st.kth) {
-                st.list = insert_desc(st.list, x);
-                st.kth = read_lane(st.list, kk - 1);
-            }
-        } while (m);
+    const int lane = lane_id();
+    for (int base = 0; base < cnt; base += kWave) {
+        const u64 key = (base + lane < cnt) ? stage[base + lane] : 0ull;
+        list = merge_desc<u64>(list, sort64_desc<u64>(key));
     }
+    return list;
+}
+
+__device__ __forceinline__ void flush_stage(RowTop &st, u64 *stage, int &cnt, int kk)
+{
+    st.list = fold_stage(st.list, stage, cnt);
+    cnt = 0;
     refresh_threshold(st, kk);
+}
+
+// Wave-wide: every lane offers one element; m = ballot of the lanes whose sum may belong to
+// the row's top k (m != 0).  Lane l's coordinate is flat0 + l*lane_stride.
+__device__ __forceinline__ void stage_candidates(RowTop &st, u64 *stage, int &cnt, float s, u64 m,
+                                                 uint32_t flat0, uint32_t lane_stride, int kk)
+{
+    const int n = __popcll(m);
+    if (cnt + n > kStageCap) flush_stage(st, stage, cnt, kk);
+    const int lane = lane_id();
+    const int pos = cnt + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+    if ((m >> lane) & 1ull) stage[pos] = make_key(s, flat0 + (uint32_t)lane * lane_stride);
+    cnt += n;
 }
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -138,9 +149,14 @@ __device__ __forceinline__ v4f neg_inf4()
     return v4f{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
 }
 
+// max of four finite-or-infinite floats in two instructions (the inputs are never NaN, so the
+// quieting moves a generic fmaxf would add are not needed)
 __device__ __forceinline__ float max4(const v4f &x)
 {
-    return fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+    float t, m;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(t) : "v"(x.x), "v"(x.y), "v"(x.z));
+    asm("v_max_f32 %0, %1, %2" : "=v"(m) : "v"(t), "v"(x.w));
+    return m;
 }
 
 // The log-probs are read exactly once: non-temporal loads keep them from displacing
@@ -182,7 +198,8 @@ __device__ __forceinline__ void block_eos(v4f (&x)[U], int rel, int lane)
 // LDS shared by the waves of one row's workgroup during the stream phase.
 struct StreamSmem {
     u64 wl[kWavesPerBlock][kWave];      // the waves' lists, for the final merge
-    float boot[kWavesPerBlock][kWave];  // sorted per-lane maxima of every wave's first tile
+    u64 stage[kWavesPerBlock][kStageCap];   // candidates parked between flushes
+    uint32_t boot[kWavesPerBlock][kWave];   // sorted per-lane maxima of every wave's first tile (order images)
     unsigned int thr;                   // best bound any wave has published (order-preserving u32)
 };
 
@@ -221,7 +238,7 @@ __device__ __forceinline__ void stream_row(const float *__restrict__ row, int V,
 #pragma unroll
     for (int u = 0; u < U; ++u) nxt[u] = neg_inf4();
     int tl = wave;
-    float boot = -INFINITY;
+    uint32_t boot = ord_from_float(-INFINITY);
     if (tl < ntiles) {
         load_tile<U>(vec, nv, tl, lane, cur);
         if (nwaves + tl < ntiles) load_tile<U>(vec, nv, tl + nwaves, lane, nxt);
@@ -229,48 +246,62 @@ __device__ __forceinline__ void stream_row(const float *__restrict__ row, int V,
         if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(cur, rel, lane);
         float lane_max = max4(cur[0]);
 #pragma unroll
-        for (int u = 1; u < U; ++u) lane_max = fmaxf(lane_max, max4(cur[u]));
-        boot = sort64_desc_f32(prev + lane_max);
+        for (int u = 1; u < U; ++u) {
+            const float mu = max4(cur[u]);
+            asm("v_max_f32 %0, %1, %2" : "=v"(lane_max) : "v"(lane_max), "v"(mu));
+        }
+        boot = sort64_desc<uint32_t>(ord_from_float(prev + lane_max));
     }
     if (nwaves > 1) {
         sm.boot[wave][lane] = boot;
         __syncthreads();
         for (int w = 0; w < nwaves; ++w)
-            if (w != wave) boot = merge_desc_f32(boot, sm.boot[w][lane]);
+            if (w != wave) boot = merge_desc<uint32_t>(boot, sm.boot[w][lane]);
     }
-    st.floor = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(boot), kk - 1));
+    st.floor = float_from_ord((uint32_t)__builtin_amdgcn_readlane((int)boot, kk - 1));
     st.thr = fmaxf(st.floor, kLowestFinite);
-    while (tl < ntiles) {
-        const int nx = tl + nwaves;
+    u64 *stage = sm.stage[wave];
+    int cnt = 0;
+    // one tile: test its U float4 groups, park what may belong to the top k
+    auto examine = [&](const v4f (&t)[U], int tile) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const v4f x = cur[u];
+            const v4f x = t[u];
             if (__any(prev + max4(x) >= st.thr)) {
-                const uint32_t flat0 = flat_base + (uint32_t)(head + 4 * ((tl * U + u) * kWave));
+                const uint32_t flat0 = flat_base + (uint32_t)(head + 4 * ((tile * U + u) * kWave));
                 const float s0 = prev + x.x, s1 = prev + x.y, s2 = prev + x.z, s3 = prev + x.w;
                 const u64 m0 = __ballot(s0 >= st.thr);
-                if (m0) consider(st, s0, m0, flat0, 4u, kk);
+                if (m0) stage_candidates(st, stage, cnt, s0, m0, flat0, 4u, kk);
                 const u64 m1 = __ballot(s1 >= st.thr);
-                if (m1) consider(st, s1, m1, flat0 + 1u, 4u, kk);
+                if (m1) stage_candidates(st, stage, cnt, s1, m1, flat0 + 1u, 4u, kk);
                 const u64 m2 = __ballot(s2 >= st.thr);
-                if (m2) consider(st, s2, m2, flat0 + 2u, 4u, kk);
+                if (m2) stage_candidates(st, stage, cnt, s2, m2, flat0 + 2u, 4u, kk);
                 const u64 m3 = __ballot(s3 >= st.thr);
-                if (m3) consider(st, s3, m3, flat0 + 3u, 4u, kk);
-                if (nwaves > 1 && lane == 0 && st.kth != 0) atomicMax(&sm.thr, ord_from_float(st.thr));
+                if (m3) stage_candidates(st, stage, cnt, s3, m3, flat0 + 3u, 4u, kk);
             }
         }
-        if (nx < ntiles) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) cur[u] = nxt[u];
-            if (nx + nwaves < ntiles) load_tile<U>(vec, nv, nx + nwaves, lane, nxt);
-            const int rel = eos_rel0 - nx * (4 * kWave * U);
-            if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(cur, rel, lane);
+    };
+    // after a tile: start the load that refills its registers (two tiles ahead) and make the
+    // other buffer ready (end-of-sentence mask, freshest shared bound)
+    auto advance = [&](v4f (&done)[U], v4f (&next)[U], int next_tile) {
+        if (next_tile + nwaves < ntiles) load_tile<U>(vec, nv, next_tile + nwaves, lane, done);
+        if (next_tile < ntiles) {
+            const int rel = eos_rel0 - next_tile * (4 * kWave * U);
+            if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(next, rel, lane);
             if (nwaves > 1) {
                 st.floor = fmaxf(st.floor, float_from_ord(sm.thr));
                 st.thr = fmaxf(st.thr, st.floor);
             }
         }
-        tl = nx;
+    };
+    while (tl < ntiles) {
+        examine(cur, tl);
+        advance(cur, nxt, tl + nwaves);
+        tl += nwaves;
+        if (tl >= ntiles) break;
+        examine(nxt, tl);
+        advance(nxt, cur, tl + nwaves);
+        tl += nwaves;
     }
     // elements before the first / after the last 16-byte aligned group (rows whose
     // length or start is not a multiple of four floats): at most 3 + 3, one per lane
@@ -284,13 +315,12 @@ __device__ __forceinline__ void stream_row(const float *__restrict__ row, int V,
             m &= m - 1;
             const int wl = l < head ? l : head + (nv << 2) + (l - head);
             const uint32_t sbits = (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(s), l);
-            const u64 x = make_key_uniform(sbits, flat_base + (uint32_t)wl);
-            if (x > st.kth) {
-                st.list = insert_desc(st.list, x);
-                refresh_threshold(st, kk);
-            }
+            if (cnt + 1 > kStageCap) flush_stage(st, stage, cnt, kk);
+            if (lane == 0) stage[cnt] = make_key_uniform(sbits, flat_base + (uint32_t)wl);
+            cnt += 1;
         }
     }
+    if (cnt > 0) flush_stage(st, stage, cnt, kk);
 }
 
 // ---------------------------------------------------------------------------
@@ -455,7 +485,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     for (int h = wave; h < k; h += kWavesPerBlock) {
         const u64 L = p.rowlists[((size_t)b * k + h) * kWave + lane];
         if (lane == 0) sm.rb[h] = L;                  // source 3: the row's best (item 3)
-        acc = merge_desc(acc, L);
+        acc = merge_desc<u64>(acc, L);
     }
     sm.wl[wave][lane] = acc;
     const int ncand_max = k * (P + 2);
@@ -464,7 +494,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     for (int i = tid; i < npad; i += kBlock) sortbuf[i] = 0;
     __syncthreads();
     if (wave == 0) {
-        for (int w = 1; w < kWavesPerBlock; ++w) acc = merge_desc(acc, sm.wl[w][lane]);
+        for (int w = 1; w < kWavesPerBlock; ++w) acc = merge_desc<u64>(acc, sm.wl[w][lane]);
         sm.t1[lane] = lane < k ? acc : 0ull;
     }
     __syncthreads();

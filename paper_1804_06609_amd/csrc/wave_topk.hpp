@@ -6,9 +6,11 @@
 // the flat coordinate h*V+w, so "greater key" means "higher score, then lower
 // coordinate" - the tie rule of the step - and no two live keys are equal.
 //
-// Lane exchanges use DPP (quad permutes, row mirrors, wave shift) inside a row
-// of 16 lanes and the gfx950 permlane16/32 swaps across rows, so a compare-
-// exchange stage costs a handful of VALU instructions and never touches LDS.
+// Lane exchanges: DPP (quad permutes, row mirrors, wave shift) where one VALU move does it,
+// ds_swizzle (the LDS crossbar, no memory access, issued outside the VALU) for the other
+// patterns inside 32 lanes, and the gfx950 permlane32 swap across the wave's halves.  A
+// compare-exchange stage is then one 64-bit compare and two selects on the VALU; the
+// direction of each lane is a loop-invariant lane mask folded in with a scalar xor.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -65,14 +67,14 @@ constexpr int kDppHalfMirror = 0x141; // lane ^ 7
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_mov(uint32_t v)
 {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xf, 0xf, true);
 }
 
-// value held by lane (lane ^ 16): rows of 16 lanes are exchanged pairwise
-__device__ __forceinline__ uint32_t xor16_u32(uint32_t v)
+// lane' = ((lane & 31) ^ X) inside each half of the wave
+template <int X>
+__device__ __forceinline__ uint32_t swizzle_xor_u32(uint32_t v)
 {
-    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-    return (lane_id() & 16) ? r[0] : r[1];
+    return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (X << 10));
 }
 
 // value held by lane (lane ^ 32): the wave's halves are exchanged
@@ -88,10 +90,8 @@ __device__ __forceinline__ uint32_t xor_lane_u32(uint32_t v)
 {
     if constexpr (J == 1) return dpp_mov<kDppXor1>(v);
     else if constexpr (J == 2) return dpp_mov<kDppXor2>(v);
-    else if constexpr (J == 4) return dpp_mov<kDppQuadRev>(dpp_mov<kDppHalfMirror>(v));
-    else if constexpr (J == 8) return dpp_mov<kDppHalfMirror>(dpp_mov<kDppRowMirror>(v));
-    else if constexpr (J == 16) return xor16_u32(v);
-    else return xor32_u32(v);
+    else if constexpr (J == 32) return xor32_u32(v);
+    else return swizzle_xor_u32<J>(v);
 }
 
 // value held by the mirror lane inside blocks of S lanes: lane ^ (S-1)
@@ -102,8 +102,8 @@ __device__ __forceinline__ uint32_t flip_lane_u32(uint32_t v)
     else if constexpr (S == 4) return dpp_mov<kDppQuadRev>(v);
     else if constexpr (S == 8) return dpp_mov<kDppHalfMirror>(v);
     else if constexpr (S == 16) return dpp_mov<kDppRowMirror>(v);
-    else if constexpr (S == 32) return dpp_mov<kDppRowMirror>(xor16_u32(v));
-    else return dpp_mov<kDppRowMirror>(xor16_u32(xor32_u32(v)));
+    else if constexpr (S == 32) return swizzle_xor_u32<31>(v);
+    else return swizzle_xor_u32<31>(xor32_u32(v));
 }
 
 template <int J>
@@ -118,54 +118,72 @@ __device__ __forceinline__ u64 flip_lane(u64 v)
     return ((u64)flip_lane_u32<S>((uint32_t)(v >> 32)) << 32) | flip_lane_u32<S>((uint32_t)v);
 }
 
-// ---- compare-exchange networks ------------------------------------------------
-// half-cleaner at distance J: the lower lane of each pair keeps the greater key
-template <int J>
-__device__ __forceinline__ u64 clean_desc(u64 key)
+// ---- compare-exchange networks (T = u64 keys or u32 order-preserving images) ---------
+template <typename T, int J>
+__device__ __forceinline__ T xor_lane_t(T v)
 {
-    const u64 other = xor_lane<J>(key);
-    return ((lane_id() & J) == 0) ? umax64(key, other) : umin64(key, other);
+    if constexpr (sizeof(T) == 8) return xor_lane<J>(v);
+    else return xor_lane_u32<J>(v);
+}
+
+template <typename T, int S>
+__device__ __forceinline__ T flip_lane_t(T v)
+{
+    if constexpr (sizeof(T) == 8) return flip_lane<S>(v);
+    else return flip_lane_u32<S>(v);
+}
+
+// half-cleaner at distance J: the lower lane of each pair keeps the greater value
+template <typename T, int J>
+__device__ __forceinline__ T clean_desc(T v)
+{
+    const T other = xor_lane_t<T, J>(v);
+    const bool upper = (lane_id() & J) != 0;
+    return ((v < other) != upper) ? other : v;
 }
 
 // sorts a bitonic run inside every block of S lanes, decreasing
-template <int S>
-__device__ __forceinline__ u64 bitonic_finish_desc(u64 key)
+template <typename T, int S>
+__device__ __forceinline__ T bitonic_finish_desc(T v)
 {
-    if constexpr (S >= 64) key = clean_desc<32>(key);
-    if constexpr (S >= 32) key = clean_desc<16>(key);
-    if constexpr (S >= 16) key = clean_desc<8>(key);
-    if constexpr (S >= 8) key = clean_desc<4>(key);
-    if constexpr (S >= 4) key = clean_desc<2>(key);
-    if constexpr (S >= 2) key = clean_desc<1>(key);
-    return key;
+    if constexpr (S >= 64) v = clean_desc<T, 32>(v);
+    if constexpr (S >= 32) v = clean_desc<T, 16>(v);
+    if constexpr (S >= 16) v = clean_desc<T, 8>(v);
+    if constexpr (S >= 8) v = clean_desc<T, 4>(v);
+    if constexpr (S >= 4) v = clean_desc<T, 2>(v);
+    if constexpr (S >= 2) v = clean_desc<T, 1>(v);
+    return v;
 }
 
 // merges the two decreasing halves of every block of S lanes into one decreasing block
-template <int S>
-__device__ __forceinline__ u64 merge_halves_desc(u64 key)
+template <typename T, int S>
+__device__ __forceinline__ T merge_halves_desc(T v)
 {
-    const u64 other = flip_lane<S>(key);
-    key = ((lane_id() & (S >> 1)) == 0) ? umax64(key, other) : umin64(key, other);
-    return bitonic_finish_desc<(S >> 1)>(key);
+    const T other = flip_lane_t<T, S>(v);
+    const bool upper = (lane_id() & (S >> 1)) != 0;
+    v = ((v < other) != upper) ? other : v;
+    return bitonic_finish_desc<T, (S >> 1)>(v);
 }
 
-// Full sort of one key per lane, decreasing by lane.
-__device__ __forceinline__ u64 sort64_desc(u64 key)
+// Full sort of one value per lane, decreasing by lane.
+template <typename T>
+__device__ __forceinline__ T sort64_desc(T v)
 {
-    key = merge_halves_desc<2>(key);
-    key = merge_halves_desc<4>(key);
-    key = merge_halves_desc<8>(key);
-    key = merge_halves_desc<16>(key);
-    key = merge_halves_desc<32>(key);
-    key = merge_halves_desc<64>(key);
-    return key;
+    v = merge_halves_desc<T, 2>(v);
+    v = merge_halves_desc<T, 4>(v);
+    v = merge_halves_desc<T, 8>(v);
+    v = merge_halves_desc<T, 16>(v);
+    v = merge_halves_desc<T, 32>(v);
+    v = merge_halves_desc<T, 64>(v);
+    return v;
 }
 
 // a, b: decreasing lists.  Returns the 64 greatest of their union, decreasing.
-__device__ __forceinline__ u64 merge_desc(u64 a, u64 b)
+template <typename T>
+__device__ __forceinline__ T merge_desc(T a, T b)
 {
-    const u64 c = umax64(a, flip_lane<64>(b));          // bitonic, holds the top 64
-    return bitonic_finish_desc<64>(c);
+    const T b_rev = flip_lane_t<T, 64>(b);
+    return bitonic_finish_desc<T, 64>(a > b_rev ? a : b_rev);   // bitonic, holds the top 64
 }
 
 // Insert the wave-uniform key x (x != 0, not already present) into a decreasing list;
@@ -177,52 +195,6 @@ __device__ __forceinline__ u64 insert_desc(u64 list, u64 x)
     const bool keep = list > x;
     const bool prev_keeps = (lane_id() == 0) || (up > x);
     return keep ? list : (prev_keeps ? x : up);
-}
-
-// ---- the same network on fp32 values (no NaNs) --------------------------------
-template <int J>
-__device__ __forceinline__ float clean_desc_f32(float v)
-{
-    const float other = __uint_as_float(xor_lane_u32<J>(__float_as_uint(v)));
-    return ((lane_id() & J) == 0) ? fmaxf(v, other) : fminf(v, other);
-}
-
-template <int S>
-__device__ __forceinline__ float bitonic_finish_desc_f32(float v)
-{
-    if constexpr (S >= 64) v = clean_desc_f32<32>(v);
-    if constexpr (S >= 32) v = clean_desc_f32<16>(v);
-    if constexpr (S >= 16) v = clean_desc_f32<8>(v);
-    if constexpr (S >= 8) v = clean_desc_f32<4>(v);
-    if constexpr (S >= 4) v = clean_desc_f32<2>(v);
-    if constexpr (S >= 2) v = clean_desc_f32<1>(v);
-    return v;
-}
-
-template <int S>
-__device__ __forceinline__ float merge_halves_desc_f32(float v)
-{
-    const float other = __uint_as_float(flip_lane_u32<S>(__float_as_uint(v)));
-    v = ((lane_id() & (S >> 1)) == 0) ? fmaxf(v, other) : fminf(v, other);
-    return bitonic_finish_desc_f32<(S >> 1)>(v);
-}
-
-__device__ __forceinline__ float sort64_desc_f32(float v)
-{
-    v = merge_halves_desc_f32<2>(v);
-    v = merge_halves_desc_f32<4>(v);
-    v = merge_halves_desc_f32<8>(v);
-    v = merge_halves_desc_f32<16>(v);
-    v = merge_halves_desc_f32<32>(v);
-    v = merge_halves_desc_f32<64>(v);
-    return v;
-}
-
-// a, b: decreasing.  The 64 greatest of their union, decreasing.
-__device__ __forceinline__ float merge_desc_f32(float a, float b)
-{
-    const float b_rev = __uint_as_float(flip_lane_u32<64>(__float_as_uint(b)));
-    return bitonic_finish_desc_f32<64>(fmaxf(a, b_rev));
 }
 
 // Inclusive prefix sum over the lanes.
