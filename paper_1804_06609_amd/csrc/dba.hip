@@ -29,11 +29,14 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
     const int nwaves = (int)(blockDim.x >> 6);
+    const bool gatherer = wave == nwaves - 1;     // this wave also fetches the constraint tokens
 
     // the row's hypothesis: wave-uniform by construction, made so for the compiler
+    const int32_t cw = gatherer ? p.cw_cur[(size_t)row * kMaxCons + lane] : -1;
     const float prev = __uint_as_float(
         (uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(p.score_cur[row])));
     const int fin = __builtin_amdgcn_readfirstlane((int)p.fin_cur[row]);
+    const float *__restrict__ logp_row = p.logp + (size_t)row * (size_t)p.V;
 
     RowTop st;
     st.list = 0;
@@ -42,19 +45,29 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
     st.thr = kLowestFinite;
     if (threadIdx.x == 0) sm.thr = ord_from_float(-INFINITY);
     __syncthreads();
-    if (prev > -INFINITY && !fin) {
-        const int P = p.nphr[b];
-        const int C = p.phr_off[(size_t)b * (kMaxCons + 1) + P];
-        const int nmet = __popcll(p.met_cur[row]);
+    u64 ckey = 0;
+    if (prev > -INFINITY && !(fin & kFinFinished)) {
+        // Alg. 2 inner loop / Sec. 3.1 item 2: the hypothesis extended by each constraint token
+        // it may place now.  The table was prepared when the hypothesis was created; only the
+        // log-prob has to be fetched (one 4-byte read per token, in flight during the stream).
+        float cx = -INFINITY;
+        int cbank = 0;
+        if (cw >= 0) {
+            cx = logp_row[cw];
+            cbank = p.cb_cur[(size_t)row * kMaxCons + lane];
+        }
         // Sec. 3.3: no end-of-sentence before all constraints are met
-        const int eos_block = __builtin_amdgcn_readfirstlane(nmet < C ? p.eos_id : -1);
-        stream_row<U>(p.logp + (size_t)row * (size_t)p.V, p.V, prev, eos_block,
-                      (uint32_t)h * (uint32_t)p.V, p.k, wave, nwaves, sm, st);
+        const int eos_block = (fin & kFinEosBlocked) ? p.eos_id : -1;
+        stream_row<U>(logp_row, p.V, prev, eos_block, (uint32_t)h * (uint32_t)p.V, p.k, wave, nwaves, sm, st);
+        const float cs = prev + cx;
+        if (cw >= 0 && cs > -INFINITY)
+            ckey = pack_sel(p.met_bits, cbank, ord_from_float(cs), (uint32_t)h * (uint32_t)p.V + (uint32_t)cw);
     } else if (prev > -INFINITY && wave == 0 && lane == 0) {
         // a finished hypothesis stays on the beam: its one continuation is the pad token
         // at log-prob +0.0, score carried unchanged
         st.list = make_key(prev + 0.0f, (uint32_t)h * (uint32_t)p.V + (uint32_t)p.pad_id);
     }
+    if (gatherer) p.conskeys[(size_t)row * kMaxCons + lane] = ckey;
     if (nwaves > 1) {
         sm.wl[wave][lane] = st.list;
         __syncthreads();
@@ -97,19 +110,40 @@ __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float
     fout[(size_t)i * 64 + lane] = float_from_ord(sort64_desc<uint32_t>(ord_from_float(vals[(size_t)i * 64 + lane])));
 }
 
-// decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0
-__global__ void dba_init_state_kernel(int B, int k, float *score, u64 *met, int32_t *ipq,
-                                      int32_t *len, uint8_t *fin, unsigned int *counters)
+// decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0.
+// Grid: one wavefront per sentence.
+__global__ void dba_init_state_kernel(int B, int k, const int32_t *cons_tok, const int32_t *phr_off,
+                                      const int32_t *nphr, float *score, u64 *met, int32_t *ipq,
+                                      int32_t *len, uint8_t *fin, u64 *inc, int32_t *nxt, int32_t *cw,
+                                      uint8_t *cb, unsigned int *counters)
 {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < B * k) {
-        score[i] = (i % k == 0) ? 0.0f : -INFINITY;
-        met[i] = 0;
-        ipq[i] = -1;
-        len[i] = 0;
-        fin[i] = 0;
+    __shared__ ConsTab ct;
+    const int b = blockIdx.x;
+    const int lane = lane_id();
+    ct.tok[lane] = cons_tok[(size_t)b * kMaxCons + lane];
+    ct.poff[lane] = phr_off[(size_t)b * (kMaxCons + 1) + lane];
+    if (lane == 0) ct.poff[kMaxCons] = phr_off[(size_t)b * (kMaxCons + 1) + kMaxCons];
+    __syncthreads();
+    const int P = nphr[b];
+    const int C = ct.poff[P];
+    for (int h = lane; h < k; h += kWave) {
+        const size_t o = (size_t)b * k + h;
+        score[o] = h == 0 ? 0.0f : -INFINITY;
+        met[o] = 0;
+        ipq[o] = -1;
+        len[o] = 0;
+        fin[o] = (uint8_t)((h == 0 && C > 0) ? kFinEosBlocked : 0);
+        inc[o] = (h == 0 && P > 0) ? (P == 64 ? ~0ull : ((1ull << P) - 1ull)) : 0ull;
+        nxt[o] = -1;
     }
-    if (i < B) counters[i] = 0;
+    for (int h = 0; h < k; ++h) {
+        int w = -1, bank = 0;
+        if (h == 0) next_token_entry(ct, P, 0ull, -1, 0, lane, w, bank);
+        const size_t o = ((size_t)b * k + h) * kMaxCons + lane;
+        cw[o] = w;
+        cb[o] = (uint8_t)bank;
+    }
+    if (lane == 0) counters[b] = 0;
 }
 
 // End of decoding (Sec. 3.3, length normalisation of Sec. 4): one thread per sentence.
@@ -131,7 +165,7 @@ __global__ void dba_finalize_kernel(int B, int k, int T, int N, int pad_id,
     int best = -1;
     float bestq = 0.0f;
     for (int h = 0; h < k; ++h) {
-        if (!(score[o + h] > -INFINITY) || !fin[o + h]) continue;
+        if (!(score[o + h] > -INFINITY) || !(fin[o + h] & kFinFinished)) continue;
         const float q = __fdiv_rn(score[o + h], (float)len[o + h]);
         if (best < 0 || q > bestq) {
             best = h;
@@ -189,8 +223,8 @@ thread_local char g_init_error[256] = "";
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t score[2], met[2], ipq[2], len[2], fin[2];
-    size_t cons_tok, phr_off, nphr, rowlists, counters;
+    size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2], cw[2], cb[2];
+    size_t cons_tok, phr_off, nphr, sfl, bloom, rowlists, conskeys, counters;
     size_t hist_token, hist_backptr;
     size_t fin_tokens, fin_len, fin_score, fin_status;
     size_t total;
@@ -211,11 +245,18 @@ Layout make_layout(size_t B, size_t k, size_t N)
         L.ipq[i] = take(B * k * sizeof(int32_t));
         L.len[i] = take(B * k * sizeof(int32_t));
         L.fin[i] = take(B * k);
+        L.inc[i] = take(B * k * sizeof(u64));
+        L.nxt[i] = take(B * k * sizeof(int32_t));
+        L.cw[i] = take(B * k * kMaxCons * sizeof(int32_t));
+        L.cb[i] = take(B * k * kMaxCons);
     }
     L.cons_tok = take(B * kMaxCons * sizeof(int32_t));
     L.phr_off = take(B * (kMaxCons + 1) * sizeof(int32_t));
     L.nphr = take(B * sizeof(int32_t));
+    L.sfl = take(B * kMaxCons * sizeof(u64));
+    L.bloom = take(B * sizeof(u64));
     L.rowlists = take(B * k * kWave * sizeof(u64));
+    L.conskeys = take(B * k * kMaxCons * sizeof(u64));
     L.counters = take(B * sizeof(unsigned int));
     L.hist_token = take(N * B * k * sizeof(int32_t));
     L.hist_backptr = take(N * B * k * sizeof(int32_t));
@@ -241,7 +282,6 @@ struct dba_ctx {
     int met_bits;
     int max_phrases;
     int steps;
-    int fused;
     int unroll;
     int waves;
     size_t dyn_smem;
@@ -314,6 +354,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     if (sent_offsets[0] != 0 || phrase_offsets[0] != 0)
         return fail(nullptr, DBA_EINVAL, "dba_init: offsets must start at 0");
     std::vector<int32_t> tok((size_t)B * kMaxCons, 0), off((size_t)B * (kMaxCons + 1), 0), nph(B, 0);
+    std::vector<u64> sfl((size_t)B * kMaxCons, 0), bloom(B, 0);
     int max_tokens = 0, max_phrases = 0;
     for (int b = 0; b < B; ++b) {
         const int p0 = sent_offsets[b], p1 = sent_offsets[b + 1];
@@ -341,6 +382,15 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         }
         off[(size_t)b * (kMaxCons + 1) + (p1 - p0)] = n;
         nph[b] = p1 - p0;
+        // lookup aids for the kernels (layout only): which lower phrases share a phrase's first
+        // token, and a 64-bit filter over the first tokens
+        for (int j = 0; j < p1 - p0; ++j) {
+            const int fj = tok[(size_t)b * kMaxCons + off[(size_t)b * (kMaxCons + 1) + j]];
+            bloom[b] |= 1ull << (fj & 63);
+            for (int j2 = 0; j2 < j; ++j2)
+                if (tok[(size_t)b * kMaxCons + off[(size_t)b * (kMaxCons + 1) + j2]] == fj)
+                    sfl[(size_t)b * kMaxCons + j] |= 1ull << j2;
+        }
         if (n > max_tokens) max_tokens = n;
         if (p1 - p0 > max_phrases) max_phrases = p1 - p0;
     }
@@ -364,7 +414,6 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->ws = static_cast<unsigned char *>(workspace_dev);
     c->L = L;
     c->stream = static_cast<hipStream_t>(hip_stream);
-    c->fused = 0;
     c->unroll = env_int("DBA_UNROLL", 4);
     c->waves = env_int("DBA_WAVES", 4);
     if (c->waves != 1 && c->waves != 2 && c->waves != 4) c->waves = 4;
@@ -378,11 +427,17 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         e = hipMemcpyAsync(at<int32_t>(c, L.phr_off), off.data(), off.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess)
         e = hipMemcpyAsync(at<int32_t>(c, L.nphr), nph.data(), nph.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(at<u64>(c, L.sfl), sfl.data(), sfl.size() * 8, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(at<u64>(c, L.bloom), bloom.data(), bloom.size() * 8, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) {
-        const int n = B * k;
-        dba_init_state_kernel<<<(n + 255) / 256, 256, 0, c->stream>>>(
-            B, k, at<float>(c, L.score[0]), at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]),
-            at<int32_t>(c, L.len[0]), at<uint8_t>(c, L.fin[0]), at<unsigned int>(c, L.counters));
+        dba_init_state_kernel<<<dim3((unsigned)B), dim3(kWave), 0, c->stream>>>(
+            B, k, at<int32_t>(c, L.cons_tok), at<int32_t>(c, L.phr_off), at<int32_t>(c, L.nphr),
+            at<float>(c, L.score[0]), at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]),
+            at<int32_t>(c, L.len[0]), at<uint8_t>(c, L.fin[0]), at<u64>(c, L.inc[0]),
+            at<int32_t>(c, L.nxt[0]), at<int32_t>(c, L.cw[0]), at<uint8_t>(c, L.cb[0]),
+            at<unsigned int>(c, L.counters));
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);   // host tables are freed on return
@@ -410,22 +465,32 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.B = c->B; p.k = c->k; p.V = c->V;
     p.eos_id = c->eos_id; p.pad_id = c->pad_id;
     p.met_bits = c->met_bits;
-    p.fused = c->fused;
     p.logp = logp_dev;
     p.score_cur = at<float>(c, L.score[cur]);
     p.met_cur = at<u64>(c, L.met[cur]);
     p.ipq_cur = at<int32_t>(c, L.ipq[cur]);
     p.len_cur = at<int32_t>(c, L.len[cur]);
     p.fin_cur = at<uint8_t>(c, L.fin[cur]);
+    p.inc_cur = at<u64>(c, L.inc[cur]);
+    p.nxt_cur = at<int32_t>(c, L.nxt[cur]);
+    p.cw_cur = at<int32_t>(c, L.cw[cur]);
+    p.cb_cur = at<uint8_t>(c, L.cb[cur]);
     p.score_nxt = at<float>(c, L.score[nxt]);
     p.met_nxt = at<u64>(c, L.met[nxt]);
     p.ipq_nxt = at<int32_t>(c, L.ipq[nxt]);
     p.len_nxt = at<int32_t>(c, L.len[nxt]);
     p.fin_nxt = at<uint8_t>(c, L.fin[nxt]);
+    p.inc_nxt = at<u64>(c, L.inc[nxt]);
+    p.nxt_nxt = at<int32_t>(c, L.nxt[nxt]);
+    p.cw_nxt = at<int32_t>(c, L.cw[nxt]);
+    p.cb_nxt = at<uint8_t>(c, L.cb[nxt]);
     p.cons_tok = at<int32_t>(c, L.cons_tok);
     p.phr_off = at<int32_t>(c, L.phr_off);
     p.nphr = at<int32_t>(c, L.nphr);
+    p.same_first_lower = at<u64>(c, L.sfl);
+    p.first_bloom = at<u64>(c, L.bloom);
     p.rowlists = at<u64>(c, L.rowlists);
+    p.conskeys = at<u64>(c, L.conskeys);
     p.counters = at<unsigned int>(c, L.counters);
     p.out_token = out_token_dev;
     p.out_backptr = out_backptr_dev;
@@ -502,7 +567,7 @@ DBA_API int dba_get_state(dba_ctx *c, float *score_host, uint64_t *met_mask_host
         if (inprog_phrase_host) inprog_phrase_host[i] = ipq[i] < 0 ? -1 : (ipq[i] >> 8);
         if (inprog_pos_host) inprog_pos_host[i] = ipq[i] < 0 ? 0 : (ipq[i] & 255);
         if (flags_host)
-            flags_host[i] = (uint8_t)((fin[i] ? DBA_FLAG_FINISHED : 0) | (score[i] > -INFINITY ? 0 : DBA_FLAG_DEAD));
+            flags_host[i] = (uint8_t)(((fin[i] & kFinFinished) ? DBA_FLAG_FINISHED : 0) | (score[i] > -INFINITY ? 0 : DBA_FLAG_DEAD));
     }
     return DBA_OK;
 }

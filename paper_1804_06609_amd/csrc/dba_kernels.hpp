@@ -3,14 +3,14 @@
 // Two phases per step:
 //   stream phase  one workgroup per beam row (b,h): a single pass over the V
 //                 log-probs of that row - score add, end-of-sentence mask,
-//                 exact top-64 of the row (which holds the row's best token
-//                 and its share of the sentence's top-k) - written as one
-//                 sorted 64-key list per row;
+//                 exact top-k of the row (which holds the row's best token
+//                 and its share of the sentence's top-k) written as one sorted
+//                 64-key list per row - plus the gather of the row's
+//                 expandable constraint tokens (their sums, as selection keys);
 //   merge phase   one workgroup per sentence: sentence top-k from the row
-//                 lists, constraint-token gather, state transition add(),
-//                 dedup, banks, allocation with adjustment, selection, new
-//                 beam.  In the fused launch it is run by whichever row
-//                 workgroup of the sentence finishes last.
+//                 lists, state transition add(), dedup, banks, allocation
+//                 with adjustment, selection, new beam, and the table of
+//                 tokens each new hypothesis may place at the next step.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <math.h>
@@ -24,32 +24,44 @@ constexpr int kMaxBeam = 64;
 constexpr int kMaxCons = 64;          // constraint tokens (and phrases) per sentence
 constexpr int kBlock = 256;           // threads per workgroup
 constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kSortThresh = 10;       // survivors in one wave-wide test above which a sort+merge beats serial inserts
+constexpr int kFinFinished = 1;       // beam-state flag: the hypothesis has generated end-of-sentence
+constexpr int kFinEosBlocked = 4;     // beam-state flag: constraints unmet, end-of-sentence not allowed (Sec. 3.3)
 
 struct StepParams {
     int B, k, V;
     int eos_id, pad_id;
     int met_bits;                     // width of the bank field in the packed selection key
-    int fused;                        // 1: the last row workgroup of a sentence runs the merge phase
     const float *logp;                // [B,k,V]
     // beam before the step
     const float *score_cur;           // [B,k]  (-inf: empty slot)
     const u64 *met_cur;               // [B,k]  bit i = constraint token i met
     const int32_t *ipq_cur;           // [B,k]  phrase under way * 256 + tokens met in it, or -1
     const int32_t *len_cur;           // [B,k]
-    const uint8_t *fin_cur;           // [B,k]
+    const uint8_t *fin_cur;           // [B,k]  kFin* flags
+    const u64 *inc_cur;               // [B,k]  bit j = phrase j is not complete
+    const int32_t *nxt_cur;           // [B,k]  next token of the phrase under way (-1: none)
+    const int32_t *cw_cur;            // [B,k,64] token the hypothesis may place now for phrase j (-1: none)
+    const uint8_t *cb_cur;            // [B,k,64] constraints met once it has placed that token
     // beam after the step
     float *score_nxt;
     u64 *met_nxt;
     int32_t *ipq_nxt;
     int32_t *len_nxt;
     uint8_t *fin_nxt;
+    u64 *inc_nxt;
+    int32_t *nxt_nxt;
+    int32_t *cw_nxt;
+    uint8_t *cb_nxt;
     // constraints
     const int32_t *cons_tok;          // [B,64]
     const int32_t *phr_off;           // [B,65] token offset of each phrase, phr_off[b][P] = C
     const int32_t *nphr;              // [B]
+    const u64 *same_first_lower;      // [B,64] phrase j: the lower phrases with the same first token
+    const u64 *first_bloom;           // [B] bit (w & 63) set for every phrase's first token w
     // scratch
-    u64 *rowlists;                    // [B*k,64]
+    u64 *rowlists;                    // [B*k,64] sorted top keys of every row (score image, ~flat)
+    u64 *conskeys;                    // [B*k,64] selection keys (bank, score image, ~flat) of the
+                                      //          row's expandable constraint tokens, 0 = none
     unsigned int *counters;           // [B] rows of the sentence that have delivered their list
     // outputs (each may be null)
     int32_t *out_token, *out_backptr;
@@ -58,23 +70,33 @@ struct StepParams {
     int32_t *hist_token, *hist_backptr;   // row t of the history, [B,k]
 };
 
-struct MergeSmem {
-    u64 wl[kWavesPerBlock][kWave];
-    u64 t1[kWave];
-    u64 rb[kMaxBeam];
-    u64 sel[kMaxBeam];
-    u64 met[kMaxBeam];
-    float prev[kMaxBeam];
-    int ipq[kMaxBeam];
-    int len[kMaxBeam];
+// constraints of one sentence: token ids phrase after phrase, phrase p = tok[poff[p] .. poff[p+1])
+struct ConsTab {
     int tok[kMaxCons];
     int poff[kMaxCons + 1];
+};
+
+struct MergeSmem {
+    u64 wl[kWavesPerBlock][kWave];
+    u64 rb[kMaxBeam];                 // every row's best, as a selection-key body
+    u64 sel[kMaxBeam];
+    u64 met[kMaxBeam];                // beam before the step ...
+    u64 inc[kMaxBeam];                // ... bit j = phrase j is not complete
+    u64 met2[kMaxBeam];               // beam after the step
+    float prev[kMaxBeam];
+    int ipq[kMaxBeam];
+    int nmet[kMaxBeam];
+    int nxt[kMaxBeam];                // next token of the phrase under way (-1: none under way)
+    int ipq2[kMaxBeam];
+    int len[kMaxBeam];
+    ConsTab ct;
     int cnt[kMaxCons + 1];
     int alloc[kMaxCons + 1];
     int start[kMaxCons + 1];
     unsigned char fin[kMaxBeam];
+    unsigned char fin2[kMaxBeam];
+    int ncand;
     int nsel;
-    int last;
 };
 
 // ---------------------------------------------------------------------------
@@ -328,7 +350,7 @@ __device__ __forceinline__ void stream_row(const float *__restrict__ row, int V,
 // ---------------------------------------------------------------------------
 // Token that phrase j lets the hypothesis place now, or -1: the next token of
 // the phrase under way; the first token of a phrase neither complete nor under way.
-__device__ __forceinline__ int expandable_token(const MergeSmem &sm, u64 met, int ip, int iq, int j)
+__device__ __forceinline__ int expandable_token(const ConsTab &sm, u64 met, int ip, int iq, int j)
 {
     const int o = sm.poff[j];
     if (j == ip) return sm.tok[o + iq];
@@ -339,7 +361,7 @@ __device__ __forceinline__ int expandable_token(const MergeSmem &sm, u64 met, in
 
 // State after emitting w: advance the phrase under way, or unwind it and let w
 // begin the lowest-index incomplete phrase that starts with w.
-__device__ __forceinline__ void cons_add(const MergeSmem &sm, int P, u64 &met, int &ip, int &iq, int w)
+__device__ __forceinline__ void cons_add(const ConsTab &sm, int P, u64 &met, int &ip, int &iq, int w)
 {
     if (ip >= 0) {
         const int o = sm.poff[ip];
@@ -366,6 +388,24 @@ __device__ __forceinline__ void cons_add(const MergeSmem &sm, int P, u64 &met, i
             iq = 1;
         }
         return;
+    }
+}
+
+// Entry j of the table a hypothesis carries into the next step: the token phrase j lets it
+// place (-1 if none, or if a lower phrase offers the same token - the candidate would be the
+// same coordinate) and the number of constraints met once it has placed it.
+__device__ __forceinline__ void next_token_entry(const ConsTab &ct, int P, u64 met, int ip, int iq,
+                                                 int j, int &w, int &bank)
+{
+    w = j < P ? expandable_token(ct, met, ip, iq, j) : -1;
+    for (int j2 = 0; j2 < j && w >= 0; ++j2)
+        if (expandable_token(ct, met, ip, iq, j2) == w) w = -1;
+    bank = 0;
+    if (w >= 0) {
+        u64 m2 = met;
+        int ip2 = ip, iq2 = iq;
+        cons_add(ct, P, m2, ip2, iq2, w);
+        bank = __popcll(m2);
     }
 }
 
@@ -439,129 +479,208 @@ __device__ __forceinline__ u64 pack_sel(int met_bits, int bank, uint32_t ord, ui
     return v;
 }
 
-// sorts buf[0..n) (n a power of two) in decreasing order; all threads of the block take part
-__device__ __forceinline__ void block_sort_desc(u64 *buf, int n)
+// rowlist key (score image << 32 | ~flat) -> body of a selection key (score image << fb | ~flat
+// in fb bits); order-preserving; 0 stays 0
+__device__ __forceinline__ u64 body_from_rowkey(int met_bits, u64 key)
 {
-    for (int k2 = 2; k2 <= n; k2 <<= 1) {
-        for (int j = k2 >> 1; j > 0; j >>= 1) {
-            for (int t = threadIdx.x; t < (n >> 1); t += kBlock) {
-                const int i = 2 * t - (t & (j - 1));
-                const int l = i + j;
-                const bool desc_block = (i & k2) == 0;
-                const u64 a = buf[i], c = buf[l];
-                if ((a < c) == desc_block) {
-                    buf[i] = c;
-                    buf[l] = a;
-                }
-            }
-            __syncthreads();
-        }
-    }
+    if (key == 0) return 0;
+    return pack_sel(met_bits, 0, (uint32_t)(key >> 32), key_flat(key));
 }
 
-__device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSmem &sm, u64 *sortbuf)
+// number of keys greater than x in a[0..64), a sorted in decreasing order
+__device__ __forceinline__ int count_greater64(const u64 *a, u64 x)
+{
+    if (a[63] > x) return 64;
+    int pos = 0;
+#pragma unroll
+    for (int step = 32; step >= 1; step >>= 1)
+        if (a[pos + step - 1] > x) pos += step;
+    return pos;
+}
+
+// Wave-wide: lane i holds token w (or -1).  Returns to lane i the set of phrases whose first
+// token is w, as a bit mask; ftok = this lane's phrase's first token (lane < P).  bloom has
+// bit (t & 63) set for every first token t, so most lanes are settled without a look.
+__device__ __forceinline__ u64 first_token_matches(int w, int ftok, int P, u64 bloom)
+{
+    const int lane = lane_id();
+    u64 todo = __ballot(w >= 0 && ((bloom >> (w & 63)) & 1ull));
+    u64 mine = 0;
+    while (todo) {
+        const int i = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const int wi = __builtin_amdgcn_readlane(w, i);
+        const u64 mm = __ballot(lane < P && ftok == wi);
+        if (lane == i) mine = mm;
+    }
+    return mine;
+}
+
+// Constraints met after a hypothesis (nmet met, phrase ip under way with iq tokens) emits a
+// token: is_next = it continues the phrase under way; match = phrases it could begin;
+// inc = phrases not complete.
+__device__ __forceinline__ int nmet_after(int nmet, int ip, int iq, bool is_next, u64 match, u64 inc)
+{
+    if (ip >= 0 && is_next) return nmet + 1;
+    const int base = ip >= 0 ? nmet - iq : nmet;          // a broken phrase is unwound
+    return base + ((match & inc) ? 1 : 0);
+}
+
+__device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSmem &sm, u64 *cand)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-    const int k = p.k, V = p.V;
-    const int P = p.nphr[b];
-    const int32_t *goff = p.phr_off + (size_t)b * (kMaxCons + 1);
-    const int C = goff[P];
+    const int k = p.k, V = p.V, mb = p.met_bits;
+    const int sel_shift = 64 - mb;
+    const u64 body_mask = mb ? ((1ull << sel_shift) - 1ull) : ~0ull;
+    const int fb = 32 - mb;
+    const uint32_t flatmask = fb >= 32 ? 0xFFFFFFFFu : ((1u << fb) - 1u);
 
-    if (tid <= P) sm.poff[tid] = goff[tid];
-    if (tid < C) sm.tok[tid] = p.cons_tok[(size_t)b * kMaxCons + tid];
-    if (tid <= kMaxCons) sm.cnt[tid] = 0;
-    if (tid == 0) sm.nsel = 0;
+    // ---- everything this sentence needs from memory, requested at once: every load is issued
+    // before the first one is waited for (clamped indices instead of branches) --------------
+    const int t64 = tid < kMaxCons ? tid : kMaxCons;
+    const int hs = tid < k ? tid : k - 1;
+    const size_t rs = (size_t)b * k + hs;
+    const int ld_poff = p.phr_off[(size_t)b * (kMaxCons + 1) + t64];
+    const int ld_tok = p.cons_tok[(size_t)b * kMaxCons + lane];
+    const u64 sfl = p.same_first_lower[(size_t)b * kMaxCons + lane];
+    const int P = p.nphr[b];
+    const u64 bloom = p.first_bloom[b];
+    const float ld_prev = p.score_cur[rs];
+    const u64 ld_met = p.met_cur[rs];
+    const u64 ld_inc = p.inc_cur[rs];
+    const int ld_ipq = p.ipq_cur[rs];
+    const int ld_nxt = p.nxt_cur[rs];
+    const int ld_len = p.len_cur[rs];
+    const int ld_fin = p.fin_cur[rs];
+    constexpr int kRowsPerWave = kMaxBeam / kWavesPerBlock;
+    u64 rl[kRowsPerWave], ck[kRowsPerWave];
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        const int h = wave + i * kWavesPerBlock;
+        rl[i] = 0;
+        ck[i] = 0;
+        if (h < k) {
+            rl[i] = p.rowlists[((size_t)b * k + h) * kWave + lane];
+            ck[i] = p.conskeys[((size_t)b * k + h) * kWave + lane];
+        }
+    }
+    if (tid <= kMaxCons) {
+        sm.ct.poff[tid] = ld_poff;
+        sm.cnt[tid] = 0;
+    }
+    if (tid < kMaxCons) sm.ct.tok[tid] = ld_tok;
+    if (tid == 0) {
+        sm.ncand = 0;
+        sm.nsel = 0;
+    }
     if (tid < k) {
-        const size_t r = (size_t)b * k + tid;
-        sm.prev[tid] = p.score_cur[r];
-        sm.met[tid] = p.met_cur[r];
-        sm.ipq[tid] = p.ipq_cur[r];
-        sm.len[tid] = p.len_cur[r];
-        sm.fin[tid] = p.fin_cur[r];
+        sm.prev[tid] = ld_prev;
+        sm.met[tid] = ld_met;
+        sm.inc[tid] = ld_inc;
+        sm.ipq[tid] = ld_ipq;
+        sm.nxt[tid] = ld_nxt;
+        sm.len[tid] = ld_len;
+        sm.nmet[tid] = __popcll(ld_met);
+        sm.fin[tid] = (unsigned char)(ld_fin & kFinFinished);
     }
 
-    // source 1: the sentence's k best (Sec. 3.1 item 1) = top k of the union of the row lists
+    // ---- source 1: the sentence's k best (Sec. 3.1 item 1) = top k of the union of the
+    // row lists; source 3: every row's best (item 3) = the head of its list.  A list whose
+    // head does not beat the running k-th best cannot contribute and is skipped. -----------
     u64 acc = 0;
-    for (int h = wave; h < k; h += kWavesPerBlock) {
-        const u64 L = p.rowlists[((size_t)b * k + h) * kWave + lane];
-        if (lane == 0) sm.rb[h] = L;                  // source 3: the row's best (item 3)
-        acc = merge_desc<u64>(acc, L);
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        const int h = wave + i * kWavesPerBlock;
+        if (h < k) {                                   // wave-uniform
+            if (lane == 0) sm.rb[h] = body_from_rowkey(mb, rl[i]);
+            if (i == 0) acc = rl[0];
+            else if (read_lane(rl[i], 0) > read_lane(acc, k - 1)) acc = merge_desc<u64>(acc, rl[i]);
+        }
     }
     sm.wl[wave][lane] = acc;
-    const int ncand_max = k * (P + 2);
-    int npad = kWave;
-    while (npad < ncand_max) npad <<= 1;
-    for (int i = tid; i < npad; i += kBlock) sortbuf[i] = 0;
-    __syncthreads();
-    if (wave == 0) {
-        for (int w = 1; w < kWavesPerBlock; ++w) acc = merge_desc<u64>(acc, sm.wl[w][lane]);
-        sm.t1[lane] = lane < k ? acc : 0ull;
+    __syncthreads();                                   // tables, beam and partial lists are in LDS
+
+    // this lane's phrase (lane < P): token range [po, pe) and first token
+    const int C = sm.ct.poff[P];
+    const int po = lane < P ? sm.ct.poff[lane] : 0;
+    const int pe = lane < P ? sm.ct.poff[lane + 1] : 1;
+    const int ftok = lane < P ? sm.ct.tok[po] : -1;
+    for (int w = 1; w < kWavesPerBlock; ++w) {
+        const u64 other = sm.wl[(wave + w) & (kWavesPerBlock - 1)][lane];
+        if (read_lane(other, 0) > read_lane(acc, k - 1)) acc = merge_desc<u64>(acc, other);
     }
-    __syncthreads();
+    // every wave now holds the sentence's best keys, lane i = i-th best.
+    // tau = k-th best; 0 while fewer than k finite sums exist, in which case every finite sum
+    // is among the k best already.
+    const u64 tau = body_from_rowkey(mb, read_lane(acc, k - 1));
 
-    // tau = k-th best key of the sentence; 0 while fewer than k finite sums exist, in which
-    // case every finite sum is among the k best already.
-    const u64 tau = sm.t1[k - 1];
-
-    // candidates, deduplicated by construction: the k best; a row's best unless among the
-    // k best; an expandable constraint token (item 2) unless among the k best, equal to its
-    // row's best, or offered already by a lower phrase of the same hypothesis.
-    for (int i = tid; i < ncand_max; i += kBlock) {
-        u64 key = 0;
-        int h = 0, w = 0;
-        bool valid = false;
-        if (i < k) {
-            key = sm.t1[i];
-            valid = key != 0;
-            if (valid) {
-                const uint32_t flat = key_flat(key);
-                h = (int)(flat / (uint32_t)V);
-                w = (int)(flat - (uint32_t)h * (uint32_t)V);
-            }
-        } else if (i < 2 * k) {
-            h = i - k;
-            key = sm.rb[h];
-            valid = key != 0 && tau != 0 && key < tau;
-            if (valid) w = (int)(key_flat(key) - (uint32_t)h * (uint32_t)V);
-        } else {
-            const int q = i - 2 * k;
-            h = q / P;
-            const int j = q - h * P;
-            const float pv = sm.prev[h];
-            if (pv > -INFINITY && !sm.fin[h]) {
-                const u64 met = sm.met[h];
-                const int ipq = sm.ipq[h];
-                const int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
-                const int wj = expandable_token(sm, met, ip, iq, j);
-                if (wj >= 0) {
-                    bool dup = false;
-                    for (int j2 = 0; j2 < j; ++j2) dup |= expandable_token(sm, met, ip, iq, j2) == wj;
-                    if (!dup) {
-                        const float s = pv + p.logp[((size_t)b * k + h) * (size_t)V + wj];
-                        if (s > -INFINITY) {
-                            key = make_key(s, (uint32_t)h * (uint32_t)V + (uint32_t)wj);
-                            valid = tau != 0 && key < tau && key != sm.rb[h];
-                            w = wj;
-                        }
-                    }
-                }
-            }
+    // ---- candidates, deduplicated by construction: the k best; a row's best unless among
+    // the k best; an expandable constraint token (item 2) unless among the k best or equal
+    // to its row's best (the table never offers one token twice for a hypothesis).  A wave
+    // counts its candidates, reserves room with one atomic and writes them. ---------------
+    u64 g_body = 0;
+    int g_bank = 0;
+    bool g_valid = false;
+    if (wave <= 1) {
+        // wave 0: the k best; wave 1: the rows' best.  Their bank needs add() (Sec. 3.1).
+        g_body = lane < k ? (wave == 0 ? body_from_rowkey(mb, acc) : sm.rb[lane]) : 0ull;
+        g_valid = g_body != 0 && (wave == 0 || (tau != 0 && g_body < tau));
+        int h = 0, w = -1;
+        if (g_valid) {
+            const uint32_t flat = flatmask - ((uint32_t)g_body & flatmask);
+            h = (int)(flat / (uint32_t)V);
+            w = (int)(flat - (uint32_t)h * (uint32_t)V);
         }
-        if (valid) {
-            u64 m2 = sm.met[h];
+        const u64 match = first_token_matches(w, ftok, P, bloom);
+        if (g_valid) {
+            g_bank = sm.nmet[h];
             if (!sm.fin[h]) {
                 const int ipq = sm.ipq[h];
-                int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
-                cons_add(sm, P, m2, ip, iq, w);
+                g_bank = nmet_after(g_bank, ipq < 0 ? -1 : (ipq >> 8), ipq < 0 ? 0 : (ipq & 255),
+                                    w == sm.nxt[h], match, sm.inc[h]);
             }
-            const int bank = __popcll(m2);                // bank = constraints met (Sec. 3.1)
-            sortbuf[i] = pack_sel(p.met_bits, bank, (uint32_t)(key >> 32), key_flat(key));
-            atomicAdd(&sm.cnt[bank], 1);
+        }
+    }
+    int total = __popcll(__ballot(g_valid));
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        const int h = wave + i * kWavesPerBlock;
+        if (h < k) {
+            const u64 body = ck[i] & body_mask;
+            const bool valid = ck[i] != 0 && tau != 0 && body < tau && body != sm.rb[h];
+            if (!valid) ck[i] = 0;
+            total += __popcll(__ballot(valid));
+        }
+    }
+    int at = 0;
+    if (lane == 0 && total > 0) at = atomicAdd(&sm.ncand, total);
+    at = __builtin_amdgcn_readfirstlane(at);
+    {
+        const u64 m = __ballot(g_valid);
+        if (g_valid) {
+            cand[at + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u))] =
+                mb ? (g_body | ((u64)g_bank << sel_shift)) : g_body;
+            atomicAdd(&sm.cnt[g_bank], 1);             // bank = constraints met (Sec. 3.1)
+        }
+        at += __popcll(m);
+    }
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        const int h = wave + i * kWavesPerBlock;
+        if (h < k) {
+            const u64 m = __ballot(ck[i] != 0);
+            if (ck[i] != 0) {
+                cand[at + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u))] = ck[i];
+                atomicAdd(&sm.cnt[mb ? (int)(ck[i] >> sel_shift) : 0], 1);
+            }
+            at += __popcll(m);
         }
     }
     __syncthreads();
+    const int ncand = sm.ncand;
+    const int nchunks = (ncand + kWave - 1) >> 6;
 
-    // slots per bank (Sec. 3.2) and where each bank begins in the sorted order (bank C first)
+    // ---- slots per bank (Sec. 3.2) --------------------------------------------------------
     if (wave == 0) {
         const int c = sm.cnt[lane];
         const int c64 = sm.cnt[kMaxCons];
@@ -576,64 +695,165 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         sm.start[lane] = (total63 - incl) + c64v;         // candidates in higher banks
         if (lane == 0) sm.start[kMaxCons] = 0;
     }
-    block_sort_desc(sortbuf, npad);                       // its barriers also publish alloc/start
-
-    // within a bank the best alloc[bank] are taken (Sec. 3.1/3.2)
-    const int sel_shift = 64 - p.met_bits;
-    const u64 body_mask = p.met_bits ? ((1ull << sel_shift) - 1ull) : ~0ull;
-    for (int i = tid; i < npad; i += kBlock) {
-        const u64 key = sortbuf[i];
-        if (key != 0) {
-            const int bank = p.met_bits ? (int)(key >> sel_shift) : 0;
-            if (i - sm.start[bank] < sm.alloc[bank]) {
-                const int slot = atomicAdd(&sm.nsel, 1);
-                sm.sel[slot] = key & body_mask;
+    // ---- every candidate's place in the order (bank desc, score desc, coordinate asc):
+    // chunks of 64 are sorted by one wave each (wave 0, busy with the allocation, last); a
+    // candidate's rank is its place in its own chunk plus, by binary search, the keys greater
+    // than it in every other chunk ------------------------------------------------------------
+    const int my_first = kWavesPerBlock - 1 - wave;
+    for (int c = my_first; c < nchunks; c += kWavesPerBlock) {
+        const int i = c * kWave + lane;
+        cand[i] = sort64_desc<u64>(i < ncand ? cand[i] : 0ull);
+    }
+    __syncthreads();
+    for (int c = my_first; c < nchunks; c += kWavesPerBlock) {
+        const u64 mine = cand[c * kWave + lane];
+        int rank = lane;
+        // four searches at a time, so that their LDS reads overlap
+        for (int c0 = 0; c0 < nchunks; c0 += 4) {
+            int pos[4];
+            bool full[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c2 = c0 + q < nchunks ? c0 + q : c;     // out of range: own chunk, ignored below
+                pos[q] = 0;
+                full[q] = cand[c2 * kWave + 63] > mine;
             }
+#pragma unroll
+            for (int step = 32; step >= 1; step >>= 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c2 = c0 + q < nchunks ? c0 + q : c;
+                    if (cand[c2 * kWave + pos[q] + step - 1] > mine) pos[q] += step;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (c0 + q < nchunks && c0 + q != c) rank += full[q] ? 64 : pos[q];
+        }
+        if (mine != 0) {
+            const int bank = mb ? (int)(mine >> sel_shift) : 0;
+            // within a bank the best alloc[bank] are taken (Sec. 3.1/3.2)
+            if (rank - sm.start[bank] < sm.alloc[bank]) sm.sel[atomicAdd(&sm.nsel, 1)] = mine & body_mask;
         }
     }
     __syncthreads();
 
-    // new beam, best first (Sec. 3.1); empty slots last
-    if (tid < k) {
-        const int nsel = sm.nsel;
-        int slot = tid;
+    // ---- new beam, best first (Sec. 3.1); empty slots last ---------------------------------
+    const int nsel = sm.nsel;
+    if (wave == 0) {
+        const u64 mine = sort64_desc<u64>(lane < nsel ? sm.sel[lane] : 0ull);   // lane = new slot
         int token = p.pad_id, parent = -1, length = 0, ipq2 = -1;
         float score = -INFINITY;
         u64 met2 = 0;
         uint8_t flags = 2, fin2 = 0;
-        if (tid < nsel) {
-            const u64 mine = sm.sel[tid];
-            slot = 0;
-            for (int j = 0; j < nsel; ++j) slot += sm.sel[j] > mine ? 1 : 0;
-            const int fb = 32 - p.met_bits;
-            const uint32_t flatmask = fb >= 32 ? 0xFFFFFFFFu : ((1u << fb) - 1u);
+        const bool live = lane < nsel;
+        if (live) {
             const uint32_t flat = flatmask - ((uint32_t)mine & flatmask);
-            const uint32_t ord = (uint32_t)(mine >> fb);
             parent = (int)(flat / (uint32_t)V);
             token = (int)(flat - (uint32_t)parent * (uint32_t)V);
-            score = float_from_ord(ord);
+            score = float_from_ord((uint32_t)(mine >> fb));
+        }
+        const u64 match = first_token_matches(live ? token : -1, ftok, P, bloom);
+        if (live) {
             met2 = sm.met[parent];
             const int ipq = sm.ipq[parent];
             int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
             const bool pfin = sm.fin[parent] != 0;
-            if (!pfin) cons_add(sm, P, met2, ip, iq, token);
+            if (!pfin) {
+                // add(token), Sec. 3.1: advance the phrase under way, or unwind it and let the
+                // token begin the lowest-index incomplete phrase that starts with it
+                if (ip >= 0 && token == sm.nxt[parent]) {
+                    const int o = sm.ct.poff[ip];
+                    met2 |= 1ull << (o + iq);
+                    ++iq;
+                    if (o + iq == sm.ct.poff[ip + 1]) {
+                        ip = -1;
+                        iq = 0;
+                    }
+                } else {
+                    if (ip >= 0) {
+                        met2 &= ~(((1ull << iq) - 1ull) << sm.ct.poff[ip]);
+                        ip = -1;
+                        iq = 0;
+                    }
+                    const u64 startable = match & sm.inc[parent];
+                    if (startable) {
+                        const int j = __ffsll((long long)startable) - 1;
+                        const int o = sm.ct.poff[j];
+                        met2 |= 1ull << o;
+                        if (sm.ct.poff[j + 1] - o > 1) {
+                            ip = j;
+                            iq = 1;
+                        }
+                    }
+                }
+            }
             ipq2 = ip < 0 ? -1 : ((ip << 8) | iq);
             fin2 = (pfin || token == p.eos_id) ? 1 : 0;
             length = pfin ? sm.len[parent] : sm.len[parent] + 1;
             flags = fin2;
         }
-        const size_t o = (size_t)b * k + slot;
-        p.score_nxt[o] = score;
-        p.met_nxt[o] = met2;
-        p.ipq_nxt[o] = ipq2;
-        p.len_nxt[o] = length;
-        p.fin_nxt[o] = fin2;
-        p.hist_token[o] = token;
-        p.hist_backptr[o] = parent;
-        if (p.out_token) p.out_token[o] = token;
-        if (p.out_backptr) p.out_backptr[o] = parent;
-        if (p.out_score) p.out_score[o] = score;
-        if (p.out_flags) p.out_flags[o] = flags;
+        if (lane < k) {
+            sm.met2[lane] = met2;
+            sm.ipq2[lane] = ipq2;
+            sm.fin2[lane] = (uint8_t)(fin2 | (live ? 0 : 2));
+            const size_t o = (size_t)b * k + lane;
+            p.score_nxt[o] = score;
+            p.met_nxt[o] = met2;
+            p.ipq_nxt[o] = ipq2;
+            p.len_nxt[o] = length;
+            p.fin_nxt[o] = (uint8_t)(fin2 | ((live && !fin2 && __popcll(met2) < C) ? kFinEosBlocked : 0));
+            p.hist_token[o] = token;
+            p.hist_backptr[o] = parent;
+            if (p.out_token) p.out_token[o] = token;
+            if (p.out_backptr) p.out_backptr[o] = parent;
+            if (p.out_score) p.out_score[o] = score;
+            if (p.out_flags) p.out_flags[o] = flags;
+        }
+    }
+    __syncthreads();
+
+    // ---- what every new hypothesis may place at the next step (Alg. 2 inner loop), one wave
+    // per hypothesis, one lane per phrase: the next token of the phrase under way, the first
+    // token of a phrase neither complete nor under way; of equal tokens only the lowest phrase
+    // keeps its entry (same coordinate); with it the constraints met once it is placed ------
+    for (int slot = wave; slot < k; slot += kWavesPerBlock) {
+        int w = -1, bank = 0, nxt2 = -1;
+        u64 inc2 = 0;
+        if (sm.fin2[slot] == 0) {                          // live and unfinished (wave-uniform)
+            const u64 met2 = sm.met2[slot];
+            const int ipq = sm.ipq2[slot];
+            const int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
+            const int nm = __popcll(met2);
+            nxt2 = ip < 0 ? -1 : sm.ct.tok[sm.ct.poff[ip] + iq];
+            const bool incomplete = lane < P && !((met2 >> (pe - 1)) & 1ull);
+            inc2 = __ballot(incomplete);
+            const bool offers_first = incomplete && lane != ip;
+            const u64 F = __ballot(offers_first);
+            if (lane == ip) w = nxt2;
+            else if (offers_first && !(sfl & F)) w = ftok;
+            if (ip >= 0) {
+                const u64 E = __ballot(w >= 0 && lane != ip && w == nxt2);   // at most one lane
+                if (E) {
+                    const int lowest = __ffsll((long long)E) - 1;
+                    if (lowest < ip) {
+                        if (lane == ip) w = -1;
+                    } else if (lane == lowest) {
+                        w = -1;
+                    }
+                }
+            }
+            if (w >= 0) bank = (ip < 0 || lane == ip || w == nxt2) ? nm + 1 : nm - iq + 1;
+        } else if (sm.fin2[slot] == 1) {
+            inc2 = 0;
+        }
+        const size_t o = ((size_t)b * k + slot) * kMaxCons + lane;
+        p.cw_nxt[o] = w;
+        p.cb_nxt[o] = (uint8_t)bank;
+        if (lane == 0) {
+            p.inc_nxt[(size_t)b * k + slot] = inc2;
+            p.nxt_nxt[(size_t)b * k + slot] = nxt2;
+        }
     }
 }
 
