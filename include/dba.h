@@ -22,8 +22,9 @@
  *   - One ctx is used from one host thread at a time.
  *
  * Limits (checked by dba_init): 1 <= k <= 64; constraint tokens per sentence
- * <= 64; k*V*(Cmax+1) must fit the packed sort key (k*V <= 2^(32-bits(Cmax)),
- * e.g. k*V <= 2^25 at 64 tokens, 2^26 at 32 tokens).
+ * <= 64; V <= 2^24; bits(k-1) + bits(V-1) + bits(Cmax) <= 32, where bits(x) is
+ * the width of x and Cmax the largest constraint-token count of a sentence
+ * (e.g. k = 64, 64 tokens: V <= 2^19; k = 20, 32 tokens: V <= 2^21).
  */
 #ifndef DBA_H
 #define DBA_H
@@ -80,7 +81,7 @@ DBA_API size_t dba_workspace_bytes(int B, int k, int V, int N, int max_cons_toke
  * Errors: DBA_EINVAL for sizes < 1, k > 64, k > V, ids outside [0,V),
  * eos_id == pad_id, a constraint token equal to eos_id or pad_id, an empty
  * phrase, offsets not starting at 0 / not non-decreasing, more than 64 tokens
- * in a sentence, the key-width limit above, a misaligned workspace;
+ * in a sentence, the width limit above, a misaligned workspace;
  * DBA_ENOMEM if workspace_bytes is too small; DBA_EHIP on a runtime failure.
  */
 DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int pad_id,

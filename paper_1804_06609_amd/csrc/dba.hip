@@ -31,41 +31,43 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
     const int nwaves = (int)(blockDim.x >> 6);
     const bool gatherer = wave == nwaves - 1;     // this wave also fetches the constraint tokens
 
-    // the row's hypothesis: wave-uniform by construction, made so for the compiler
-    const int32_t cw = gatherer ? p.cw_cur[(size_t)row * kMaxCons + lane] : -1;
-    const float prev = __uint_as_float(
-        (uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(p.score_cur[row])));
-    const int fin = __builtin_amdgcn_readfirstlane((int)p.fin_cur[row]);
+    // requests in the order their answers are needed: the hypothesis, its constraint-token
+    // table, then the first two tiles of the row (which need nothing of the hypothesis)
+    const float prev_ld = p.score_cur[row];
+    const int fin_ld = p.fin_cur[row];
+    const int32_t cwb = gatherer ? p.cwb_cur[(size_t)row * kMaxCons + lane] : -1;
     const float *__restrict__ logp_row = p.logp + (size_t)row * (size_t)p.V;
+    RowStream<U> rs;
+    rs.begin(logp_row, p.V, wave, nwaves);
+    if (threadIdx.x == 0) sm.thr = ord_from_float(-INFINITY);
+
+    // the row's hypothesis: wave-uniform by construction, made so for the compiler
+    const float prev = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(prev_ld)));
+    const int fin = __builtin_amdgcn_readfirstlane(fin_ld);
+    const uint32_t code_base = (uint32_t)h << p.tok_bits;
 
     RowTop st;
     st.list = 0;
     st.kth = 0;
     st.floor = -INFINITY;
     st.thr = kLowestFinite;
-    if (threadIdx.x == 0) sm.thr = ord_from_float(-INFINITY);
-    __syncthreads();
     u64 ckey = 0;
     if (prev > -INFINITY && !(fin & kFinFinished)) {
         // Alg. 2 inner loop / Sec. 3.1 item 2: the hypothesis extended by each constraint token
         // it may place now.  The table was prepared when the hypothesis was created; only the
         // log-prob has to be fetched (one 4-byte read per token, in flight during the stream).
-        float cx = -INFINITY;
-        int cbank = 0;
-        if (cw >= 0) {
-            cx = logp_row[cw];
-            cbank = p.cb_cur[(size_t)row * kMaxCons + lane];
-        }
+        const int cw = cwb >= 0 ? (cwb & 0xFFFFFF) : -1;
+        const float cx = cw >= 0 ? logp_row[cw] : -INFINITY;
         // Sec. 3.3: no end-of-sentence before all constraints are met
         const int eos_block = (fin & kFinEosBlocked) ? p.eos_id : -1;
-        stream_row<U>(logp_row, p.V, prev, eos_block, (uint32_t)h * (uint32_t)p.V, p.k, wave, nwaves, sm, st);
+        rs.run(prev, eos_block, code_base, p.k, wave, nwaves, sm, st);
         const float cs = prev + cx;
         if (cw >= 0 && cs > -INFINITY)
-            ckey = pack_sel(p.met_bits, cbank, ord_from_float(cs), (uint32_t)h * (uint32_t)p.V + (uint32_t)cw);
+            ckey = pack_sel(p.met_bits, cwb >> 24, ord_from_float(cs), code_base | (uint32_t)cw);
     } else if (prev > -INFINITY && wave == 0 && lane == 0) {
         // a finished hypothesis stays on the beam: its one continuation is the pad token
         // at log-prob +0.0, score carried unchanged
-        st.list = make_key(prev + 0.0f, (uint32_t)h * (uint32_t)p.V + (uint32_t)p.pad_id);
+        st.list = make_key(prev + 0.0f, code_base | (uint32_t)p.pad_id);
     }
     if (gatherer) p.conskeys[(size_t)row * kMaxCons + lane] = ckey;
     if (nwaves > 1) {
@@ -114,8 +116,8 @@ __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float
 // Grid: one wavefront per sentence.
 __global__ void dba_init_state_kernel(int B, int k, const int32_t *cons_tok, const int32_t *phr_off,
                                       const int32_t *nphr, float *score, u64 *met, int32_t *ipq,
-                                      int32_t *len, uint8_t *fin, u64 *inc, int32_t *nxt, int32_t *cw,
-                                      uint8_t *cb, unsigned int *counters)
+                                      int32_t *len, uint8_t *fin, u64 *inc, int32_t *nxt, int32_t *cwb,
+                                      unsigned int *counters)
 {
     __shared__ ConsTab ct;
     const int b = blockIdx.x;
@@ -139,9 +141,7 @@ __global__ void dba_init_state_kernel(int B, int k, const int32_t *cons_tok, con
     for (int h = 0; h < k; ++h) {
         int w = -1, bank = 0;
         if (h == 0) next_token_entry(ct, P, 0ull, -1, 0, lane, w, bank);
-        const size_t o = ((size_t)b * k + h) * kMaxCons + lane;
-        cw[o] = w;
-        cb[o] = (uint8_t)bank;
+        cwb[((size_t)b * k + h) * kMaxCons + lane] = w >= 0 ? ((bank << 24) | w) : -1;
     }
     if (lane == 0) counters[b] = 0;
 }
@@ -223,7 +223,7 @@ thread_local char g_init_error[256] = "";
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2], cw[2], cb[2];
+    size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2], cwb[2];
     size_t cons_tok, phr_off, nphr, sfl, bloom, rowlists, conskeys, counters;
     size_t hist_token, hist_backptr;
     size_t fin_tokens, fin_len, fin_score, fin_status;
@@ -247,8 +247,7 @@ Layout make_layout(size_t B, size_t k, size_t N)
         L.fin[i] = take(B * k);
         L.inc[i] = take(B * k * sizeof(u64));
         L.nxt[i] = take(B * k * sizeof(int32_t));
-        L.cw[i] = take(B * k * kMaxCons * sizeof(int32_t));
-        L.cb[i] = take(B * k * kMaxCons);
+        L.cwb[i] = take(B * k * kMaxCons * sizeof(int32_t));
     }
     L.cons_tok = take(B * kMaxCons * sizeof(int32_t));
     L.phr_off = take(B * (kMaxCons + 1) * sizeof(int32_t));
@@ -280,6 +279,7 @@ int bits_for(int v)   // bits needed to hold values 0..v
 struct dba_ctx {
     int B, k, V, N, eos_id, pad_id;
     int met_bits;
+    int tok_bits;
     int max_phrases;
     int steps;
     int unroll;
@@ -394,11 +394,15 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         if (n > max_tokens) max_tokens = n;
         if (p1 - p0 > max_phrases) max_phrases = p1 - p0;
     }
+    // a coordinate is (slot << tok_bits) | token; with the bank it must fit the 32 bits the
+    // selection key has beside the score
     const int met_bits = bits_for(max_tokens);
-    if ((unsigned long long)k * (unsigned long long)V > (1ull << (32 - met_bits)))
+    const int tok_bits = bits_for(V - 1) < 1 ? 1 : bits_for(V - 1);
+    const int slot_bits = bits_for(k - 1);
+    if (met_bits + slot_bits + tok_bits > 32 || tok_bits > 24)
         return fail(nullptr, DBA_EINVAL,
-                    "dba_init: k*V = %llu exceeds 2^%d, the coordinate width left by %d constraint tokens",
-                    (unsigned long long)k * V, 32 - met_bits, max_tokens);
+                    "dba_init: bits(k-1)=%d + bits(V-1)=%d + bits(max constraint tokens)=%d exceed the 32-bit "
+                    "coordinate field of the selection key (or V > 2^24)", slot_bits, tok_bits, met_bits);
 
     const Layout L = make_layout((size_t)B, (size_t)k, (size_t)N);
     if (workspace_bytes < L.total)
@@ -409,6 +413,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     memset(c, 0, sizeof *c);
     c->B = B; c->k = k; c->V = V; c->N = N; c->eos_id = eos_id; c->pad_id = pad_id;
     c->met_bits = met_bits;
+    c->tok_bits = tok_bits;
     c->max_phrases = max_phrases;
     c->steps = 0;
     c->ws = static_cast<unsigned char *>(workspace_dev);
@@ -436,8 +441,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
             B, k, at<int32_t>(c, L.cons_tok), at<int32_t>(c, L.phr_off), at<int32_t>(c, L.nphr),
             at<float>(c, L.score[0]), at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]),
             at<int32_t>(c, L.len[0]), at<uint8_t>(c, L.fin[0]), at<u64>(c, L.inc[0]),
-            at<int32_t>(c, L.nxt[0]), at<int32_t>(c, L.cw[0]), at<uint8_t>(c, L.cb[0]),
-            at<unsigned int>(c, L.counters));
+            at<int32_t>(c, L.nxt[0]), at<int32_t>(c, L.cwb[0]), at<unsigned int>(c, L.counters));
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);   // host tables are freed on return
@@ -465,6 +469,7 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.B = c->B; p.k = c->k; p.V = c->V;
     p.eos_id = c->eos_id; p.pad_id = c->pad_id;
     p.met_bits = c->met_bits;
+    p.tok_bits = c->tok_bits;
     p.logp = logp_dev;
     p.score_cur = at<float>(c, L.score[cur]);
     p.met_cur = at<u64>(c, L.met[cur]);
@@ -473,8 +478,7 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.fin_cur = at<uint8_t>(c, L.fin[cur]);
     p.inc_cur = at<u64>(c, L.inc[cur]);
     p.nxt_cur = at<int32_t>(c, L.nxt[cur]);
-    p.cw_cur = at<int32_t>(c, L.cw[cur]);
-    p.cb_cur = at<uint8_t>(c, L.cb[cur]);
+    p.cwb_cur = at<int32_t>(c, L.cwb[cur]);
     p.score_nxt = at<float>(c, L.score[nxt]);
     p.met_nxt = at<u64>(c, L.met[nxt]);
     p.ipq_nxt = at<int32_t>(c, L.ipq[nxt]);
@@ -482,8 +486,7 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.fin_nxt = at<uint8_t>(c, L.fin[nxt]);
     p.inc_nxt = at<u64>(c, L.inc[nxt]);
     p.nxt_nxt = at<int32_t>(c, L.nxt[nxt]);
-    p.cw_nxt = at<int32_t>(c, L.cw[nxt]);
-    p.cb_nxt = at<uint8_t>(c, L.cb[nxt]);
+    p.cwb_nxt = at<int32_t>(c, L.cwb[nxt]);
     p.cons_tok = at<int32_t>(c, L.cons_tok);
     p.phr_off = at<int32_t>(c, L.phr_off);
     p.nphr = at<int32_t>(c, L.nphr);

@@ -31,6 +31,7 @@ struct StepParams {
     int B, k, V;
     int eos_id, pad_id;
     int met_bits;                     // width of the bank field in the packed selection key
+    int tok_bits;                     // width of the token field of a coordinate: (h << tok_bits) | w
     const float *logp;                // [B,k,V]
     // beam before the step
     const float *score_cur;           // [B,k]  (-inf: empty slot)
@@ -40,8 +41,8 @@ struct StepParams {
     const uint8_t *fin_cur;           // [B,k]  kFin* flags
     const u64 *inc_cur;               // [B,k]  bit j = phrase j is not complete
     const int32_t *nxt_cur;           // [B,k]  next token of the phrase under way (-1: none)
-    const int32_t *cw_cur;            // [B,k,64] token the hypothesis may place now for phrase j (-1: none)
-    const uint8_t *cb_cur;            // [B,k,64] constraints met once it has placed that token
+    const int32_t *cwb_cur;           // [B,k,64] phrase j: token the hypothesis may place now, with the
+                                      //          constraints met once it has (bank << 24 | token; -1: none)
     // beam after the step
     float *score_nxt;
     u64 *met_nxt;
@@ -50,8 +51,7 @@ struct StepParams {
     uint8_t *fin_nxt;
     u64 *inc_nxt;
     int32_t *nxt_nxt;
-    int32_t *cw_nxt;
-    uint8_t *cb_nxt;
+    int32_t *cwb_nxt;
     // constraints
     const int32_t *cons_tok;          // [B,64]
     const int32_t *phr_off;           // [B,65] token offset of each phrase, phr_off[b][P] = C
@@ -242,28 +242,45 @@ struct StreamSmem {
 // through; it never drops one.  The row's best element is never below any bound, so it
 // always survives.
 template <int U>
-__device__ __forceinline__ void stream_row(const float *__restrict__ row, int V, float prev,
-                                           int eos_block, uint32_t flat_base, int kk, int wave,
-                                           int nwaves, StreamSmem &sm, RowTop &st)
+struct RowStream {
+    const float *row;
+    const v4f *vec;
+    int V, head, nv, tail, ntiles;
+    v4f cur[U], nxt[U];
+
+    // Issues the loads of this wave's first two tiles.  Needs nothing of the hypothesis, so it
+    // runs before the beam state has arrived.
+    __device__ __forceinline__ void begin(const float *__restrict__ row_, int V_, int wave, int nwaves)
+    {
+        const int lane = lane_id();
+        row = row_;
+        V = V_;
+        const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
+        head = (int)(((16u - (unsigned)(addr & 15u)) & 15u) >> 2);
+        if (head > V) head = V;
+        nv = (V - head) >> 2;
+        tail = V - head - (nv << 2);
+        vec = reinterpret_cast<const v4f *>(row + head);
+        ntiles = (nv + kWave * U - 1) / (kWave * U);
+#pragma unroll
+        for (int u = 0; u < U; ++u) nxt[u] = neg_inf4();
+        if (wave < ntiles) load_tile<U>(vec, nv, wave, lane, cur);
+        if (wave + nwaves < ntiles) load_tile<U>(vec, nv, wave + nwaves, lane, nxt);
+    }
+
+    __device__ __forceinline__ void run(float prev, int eos_block, uint32_t flat_base, int kk, int wave,
+                                        int nwaves, StreamSmem &sm, RowTop &st);
+};
+
+template <int U>
+__device__ __forceinline__ void RowStream<U>::run(float prev, int eos_block, uint32_t flat_base, int kk,
+                                                  int wave, int nwaves, StreamSmem &sm, RowTop &st)
 {
     const int lane = lane_id();
-    const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
-    int head = (int)(((16u - (unsigned)(addr & 15u)) & 15u) >> 2);
-    if (head > V) head = V;
-    const int nv = (V - head) >> 2;
-    const int tail = V - head - (nv << 2);
-    const v4f *__restrict__ vec = reinterpret_cast<const v4f *>(row + head);
-    const int ntiles = (nv + kWave * U - 1) / (kWave * U);
     const int eos_rel0 = eos_block >= 0 ? eos_block - head : -1;   // position in the aligned body
-
-    v4f cur[U], nxt[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) nxt[u] = neg_inf4();
     int tl = wave;
     uint32_t boot = ord_from_float(-INFINITY);
     if (tl < ntiles) {
-        load_tile<U>(vec, nv, tl, lane, cur);
-        if (nwaves + tl < ntiles) load_tile<U>(vec, nv, tl + nwaves, lane, nxt);
         const int rel = eos_rel0 - tl * (4 * kWave * U);
         if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(cur, rel, lane);
         float lane_max = max4(cur[0]);
@@ -529,11 +546,12 @@ __device__ __forceinline__ int nmet_after(int nmet, int ip, int iq, bool is_next
 __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSmem &sm, u64 *cand)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-    const int k = p.k, V = p.V, mb = p.met_bits;
+    const int k = p.k, mb = p.met_bits;
     const int sel_shift = 64 - mb;
     const u64 body_mask = mb ? ((1ull << sel_shift) - 1ull) : ~0ull;
     const int fb = 32 - mb;
     const uint32_t flatmask = fb >= 32 ? 0xFFFFFFFFu : ((1u << fb) - 1u);
+    const uint32_t tokmask = (1u << p.tok_bits) - 1u;
 
     // ---- everything this sentence needs from memory, requested at once: every load is issued
     // before the first one is waited for (clamped indices instead of branches) --------------
@@ -627,9 +645,9 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         g_valid = g_body != 0 && (wave == 0 || (tau != 0 && g_body < tau));
         int h = 0, w = -1;
         if (g_valid) {
-            const uint32_t flat = flatmask - ((uint32_t)g_body & flatmask);
-            h = (int)(flat / (uint32_t)V);
-            w = (int)(flat - (uint32_t)h * (uint32_t)V);
+            const uint32_t code = flatmask - ((uint32_t)g_body & flatmask);
+            h = (int)(code >> p.tok_bits);
+            w = (int)(code & tokmask);
         }
         const u64 match = first_token_matches(w, ftok, P, bloom);
         if (g_valid) {
@@ -748,9 +766,9 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         uint8_t flags = 2, fin2 = 0;
         const bool live = lane < nsel;
         if (live) {
-            const uint32_t flat = flatmask - ((uint32_t)mine & flatmask);
-            parent = (int)(flat / (uint32_t)V);
-            token = (int)(flat - (uint32_t)parent * (uint32_t)V);
+            const uint32_t code = flatmask - ((uint32_t)mine & flatmask);
+            parent = (int)(code >> p.tok_bits);
+            token = (int)(code & tokmask);
             score = float_from_ord((uint32_t)(mine >> fb));
         }
         const u64 match = first_token_matches(live ? token : -1, ftok, P, bloom);
@@ -847,9 +865,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         } else if (sm.fin2[slot] == 1) {
             inc2 = 0;
         }
-        const size_t o = ((size_t)b * k + slot) * kMaxCons + lane;
-        p.cw_nxt[o] = w;
-        p.cb_nxt[o] = (uint8_t)bank;
+        p.cwb_nxt[((size_t)b * k + slot) * kMaxCons + lane] = w >= 0 ? ((bank << 24) | w) : -1;
         if (lane == 0) {
             p.inc_nxt[(size_t)b * k + slot] = inc2;
             p.nxt_nxt[(size_t)b * k + slot] = nxt2;

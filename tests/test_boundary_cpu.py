@@ -64,7 +64,7 @@ def _init(B=1, k=5, V=1000, N=10, eos=2, pad=0, toks=(5, 6), poff=(0, 2), soff=(
     (dict(ws=0), "NULL"),
     (dict(nbytes=1024), "workspace has"),
     (dict(toks=tuple(range(4, 69 + 4)), poff=(0, 69)), "more than 64"),
-    (dict(k=64, V=600000, toks=tuple(range(4, 68)), poff=(0, 64)), "exceeds 2^"),
+    (dict(k=64, V=600000, toks=tuple(range(4, 68)), poff=(0, 64)), "exceed the 32-bit"),
 ])
 def test_init_rejects_bad_arguments(kw, frag):
     with pytest.raises(dba.DbaError) as ei:
