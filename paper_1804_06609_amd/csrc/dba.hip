@@ -16,14 +16,13 @@ using namespace dba;
 // ---------------------------------------------------------------------------
 // kernels
 // ---------------------------------------------------------------------------
-// Stream phase.  Grid: one workgroup of blockDim.x/64 waves per beam row.
-// U = float4 loads each lane keeps in flight per tile.
-template <int U>
-__global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
+// Stream phase of one beam row by one workgroup of blockDim.x/64 waves: leaves the row's sorted
+// top keys in p.rowlists and the keys of its constraint tokens in p.conskeys.
+// U = float4 loads each lane keeps in flight per tile.  PUBLISH: the two results are written
+// with device-scope atomic stores, for readers in other workgroups of the same launch.
+template <int U, bool PUBLISH>
+__device__ __forceinline__ void stream_phase(const StepParams &p, int row, StreamSmem &sm)
 {
-    __shared__ StreamSmem sm;
-
-    const int row = blockIdx.x;
     const int b = row / p.k;
     const int h = row - b * p.k;
     const int lane = lane_id();
@@ -31,11 +30,22 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
     const int nwaves = (int)(blockDim.x >> 6);
     const bool gatherer = wave == nwaves - 1;     // this wave also fetches the constraint tokens
 
-    // requests in the order their answers are needed: the hypothesis, its constraint-token
-    // table, then the first two tiles of the row (which need nothing of the hypothesis)
+    // requests in the order their answers are needed: the hypothesis, its constraint
+    // bookkeeping (one wave, one lane per phrase), then the first two tiles of the row (which
+    // need nothing of the hypothesis)
     const float prev_ld = p.score_cur[row];
     const int fin_ld = p.fin_cur[row];
-    const int32_t cwb = gatherer ? p.cwb_cur[(size_t)row * kMaxCons + lane] : -1;
+    u64 g_met = 0, g_inc = 0, g_sfl = 0;
+    int g_ipq = -1, g_nxt = -1, g_ftok = -1, g_P = 0;
+    if (gatherer) {
+        g_met = p.met_cur[row];
+        g_inc = p.inc_cur[row];
+        g_ipq = p.ipq_cur[row];
+        g_nxt = p.nxt_cur[row];
+        g_P = p.nphr[b];
+        g_ftok = p.first_tok[(size_t)b * kMaxCons + lane];
+        g_sfl = p.same_first_lower[(size_t)b * kMaxCons + lane];
+    }
     const float *__restrict__ logp_row = p.logp + (size_t)row * (size_t)p.V;
     RowStream<U> rs;
     rs.begin(logp_row, p.V, wave, nwaves);
@@ -54,22 +64,28 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
     u64 ckey = 0;
     if (prev > -INFINITY && !(fin & kFinFinished)) {
         // Alg. 2 inner loop / Sec. 3.1 item 2: the hypothesis extended by each constraint token
-        // it may place now.  The table was prepared when the hypothesis was created; only the
-        // log-prob has to be fetched (one 4-byte read per token, in flight during the stream).
-        const int cw = cwb >= 0 ? (cwb & 0xFFFFFF) : -1;
+        // it may place now; the log-prob is one 4-byte read per token, in flight during the stream
+        int cw = -1, cbank = 0;
+        if (gatherer)
+            cw = expandable_entry(g_P, __popcll(g_met), g_inc, g_ipq < 0 ? -1 : (g_ipq >> 8),
+                                  g_ipq < 0 ? 0 : (g_ipq & 255), g_nxt, g_ftok, g_sfl, cbank);
         const float cx = cw >= 0 ? logp_row[cw] : -INFINITY;
         // Sec. 3.3: no end-of-sentence before all constraints are met
         const int eos_block = (fin & kFinEosBlocked) ? p.eos_id : -1;
         rs.run(prev, eos_block, code_base, p.k, wave, nwaves, sm, st);
         const float cs = prev + cx;
         if (cw >= 0 && cs > -INFINITY)
-            ckey = pack_sel(p.met_bits, cwb >> 24, ord_from_float(cs), code_base | (uint32_t)cw);
+            ckey = pack_sel(p.met_bits, cbank, ord_from_float(cs), code_base | (uint32_t)cw);
     } else if (prev > -INFINITY && wave == 0 && lane == 0) {
         // a finished hypothesis stays on the beam: its one continuation is the pad token
         // at log-prob +0.0, score carried unchanged
         st.list = make_key(prev + 0.0f, code_base | (uint32_t)p.pad_id);
     }
-    if (gatherer) p.conskeys[(size_t)row * kMaxCons + lane] = ckey;
+    if (gatherer) {
+        u64 *dst = p.conskeys + (size_t)row * kMaxCons + lane;
+        if (PUBLISH) __hip_atomic_store(dst, ckey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *dst = ckey;
+    }
     if (nwaves > 1) {
         sm.wl[wave][lane] = st.list;
         __syncthreads();
@@ -77,8 +93,52 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
     if (wave == 0) {
         u64 acc = st.list;
         for (int w = 1; w < nwaves; ++w) acc = merge_desc<u64>(acc, sm.wl[w][lane]);
-        p.rowlists[(size_t)row * kWave + lane] = acc;
+        u64 *dst = p.rowlists + (size_t)row * kWave + lane;
+        if (PUBLISH) __hip_atomic_store(dst, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *dst = acc;
     }
+}
+
+// Two-launch form, first launch.  Grid: one workgroup per beam row.
+template <int U>
+__global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
+{
+    __shared__ StreamSmem sm;
+    stream_phase<U, false>(p, (int)blockIdx.x, sm);
+}
+
+// One-launch form.  Grid: one workgroup (256 threads) per beam row.  Every workgroup streams
+// its row; the one that delivers the last row of a sentence goes on to run that sentence's
+// merge phase, while other sentences are still streaming.
+//
+// Hand-over between workgroups without cache-wide fences: the row results are written with
+// device-scope atomic stores (written through to memory), each wave then waits for its stores
+// to be acknowledged, the workgroup meets at a barrier, and one thread bumps the sentence's
+// arrival counter with a device-scope atomic.  Whoever reads k-1 there knows all k rows have
+// arrived and reads them with device-scope atomic loads (which bypass the non-coherent
+// caches).  No workgroup ever waits for another.
+template <int U>
+__global__ __launch_bounds__(kBlock) void dba_step_fused_kernel(const StepParams p)
+{
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
+    constexpr size_t kBytes = sizeof(StreamSmem) > sizeof(MergeSmem) ? sizeof(StreamSmem) : sizeof(MergeSmem);
+    __shared__ __align__(16) unsigned char raw[kBytes];   // the phases use it one after the other
+    __shared__ int last;
+
+    const int row = (int)blockIdx.x;
+    const int b = row / p.k;
+    stream_phase<U, true>(p, row, *reinterpret_cast<StreamSmem *>(raw));
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's published stores are done
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int seen =
+            __hip_atomic_fetch_add(p.counters + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = seen == (unsigned int)(p.k - 1) ? 1 : 0;
+        if (last) __hip_atomic_store(p.counters + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!last) return;
+    merge_phase<true>(p, b, *reinterpret_cast<MergeSmem *>(raw), reinterpret_cast<u64 *>(dyn_smem));
 }
 
 // Merge phase.  Grid: one workgroup per sentence.
@@ -86,7 +146,7 @@ __global__ __launch_bounds__(kBlock) void dba_merge_kernel(const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ MergeSmem sm;
-    merge_phase(p, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
+    merge_phase<false>(p, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
 }
 
 // Diagnostic: the wavefront selection primitives on caller-provided keys, one wave per case.
@@ -112,38 +172,25 @@ __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float
     fout[(size_t)i * 64 + lane] = float_from_ord(sort64_desc<uint32_t>(ord_from_float(vals[(size_t)i * 64 + lane])));
 }
 
-// decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0.
-// Grid: one wavefront per sentence.
-__global__ void dba_init_state_kernel(int B, int k, const int32_t *cons_tok, const int32_t *phr_off,
-                                      const int32_t *nphr, float *score, u64 *met, int32_t *ipq,
-                                      int32_t *len, uint8_t *fin, u64 *inc, int32_t *nxt, int32_t *cwb,
-                                      unsigned int *counters)
+// decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0
+__global__ void dba_init_state_kernel(int B, int k, const int32_t *phr_off, const int32_t *nphr, float *score,
+                                      u64 *met, int32_t *ipq, int32_t *len, uint8_t *fin, u64 *inc,
+                                      int32_t *nxt, unsigned int *counters)
 {
-    __shared__ ConsTab ct;
-    const int b = blockIdx.x;
-    const int lane = lane_id();
-    ct.tok[lane] = cons_tok[(size_t)b * kMaxCons + lane];
-    ct.poff[lane] = phr_off[(size_t)b * (kMaxCons + 1) + lane];
-    if (lane == 0) ct.poff[kMaxCons] = phr_off[(size_t)b * (kMaxCons + 1) + kMaxCons];
-    __syncthreads();
-    const int P = nphr[b];
-    const int C = ct.poff[P];
-    for (int h = lane; h < k; h += kWave) {
-        const size_t o = (size_t)b * k + h;
-        score[o] = h == 0 ? 0.0f : -INFINITY;
-        met[o] = 0;
-        ipq[o] = -1;
-        len[o] = 0;
-        fin[o] = (uint8_t)((h == 0 && C > 0) ? kFinEosBlocked : 0);
-        inc[o] = (h == 0 && P > 0) ? (P == 64 ? ~0ull : ((1ull << P) - 1ull)) : 0ull;
-        nxt[o] = -1;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < B * k) {
+        const int b = i / k, h = i - b * k;
+        const int P = nphr[b];
+        const int C = phr_off[(size_t)b * (kMaxCons + 1) + P];
+        score[i] = h == 0 ? 0.0f : -INFINITY;
+        met[i] = 0;
+        ipq[i] = -1;
+        len[i] = 0;
+        fin[i] = (uint8_t)((h == 0 && C > 0) ? kFinEosBlocked : 0);
+        inc[i] = (h == 0 && P > 0) ? (P == 64 ? ~0ull : ((1ull << P) - 1ull)) : 0ull;
+        nxt[i] = -1;
     }
-    for (int h = 0; h < k; ++h) {
-        int w = -1, bank = 0;
-        if (h == 0) next_token_entry(ct, P, 0ull, -1, 0, lane, w, bank);
-        cwb[((size_t)b * k + h) * kMaxCons + lane] = w >= 0 ? ((bank << 24) | w) : -1;
-    }
-    if (lane == 0) counters[b] = 0;
+    if (i < B) counters[i] = 0;
 }
 
 // End of decoding (Sec. 3.3, length normalisation of Sec. 4): one thread per sentence.
@@ -223,8 +270,8 @@ thread_local char g_init_error[256] = "";
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
-    size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2], cwb[2];
-    size_t cons_tok, phr_off, nphr, sfl, bloom, rowlists, conskeys, counters;
+    size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2];
+    size_t cons_tok, phr_off, nphr, ftok, sfl, bloom, rowlists, conskeys, counters;
     size_t hist_token, hist_backptr;
     size_t fin_tokens, fin_len, fin_score, fin_status;
     size_t total;
@@ -247,11 +294,11 @@ Layout make_layout(size_t B, size_t k, size_t N)
         L.fin[i] = take(B * k);
         L.inc[i] = take(B * k * sizeof(u64));
         L.nxt[i] = take(B * k * sizeof(int32_t));
-        L.cwb[i] = take(B * k * kMaxCons * sizeof(int32_t));
     }
     L.cons_tok = take(B * kMaxCons * sizeof(int32_t));
     L.phr_off = take(B * (kMaxCons + 1) * sizeof(int32_t));
     L.nphr = take(B * sizeof(int32_t));
+    L.ftok = take(B * kMaxCons * sizeof(int32_t));
     L.sfl = take(B * kMaxCons * sizeof(u64));
     L.bloom = take(B * sizeof(u64));
     L.rowlists = take(B * k * kWave * sizeof(u64));
@@ -282,6 +329,7 @@ struct dba_ctx {
     int tok_bits;
     int max_phrases;
     int steps;
+    int fused;
     int unroll;
     int waves;
     size_t dyn_smem;
@@ -355,6 +403,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         return fail(nullptr, DBA_EINVAL, "dba_init: offsets must start at 0");
     std::vector<int32_t> tok((size_t)B * kMaxCons, 0), off((size_t)B * (kMaxCons + 1), 0), nph(B, 0);
     std::vector<u64> sfl((size_t)B * kMaxCons, 0), bloom(B, 0);
+    std::vector<int32_t> ftok((size_t)B * kMaxCons, -1);
     int max_tokens = 0, max_phrases = 0;
     for (int b = 0; b < B; ++b) {
         const int p0 = sent_offsets[b], p1 = sent_offsets[b + 1];
@@ -386,6 +435,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         // token, and a 64-bit filter over the first tokens
         for (int j = 0; j < p1 - p0; ++j) {
             const int fj = tok[(size_t)b * kMaxCons + off[(size_t)b * (kMaxCons + 1) + j]];
+            ftok[(size_t)b * kMaxCons + j] = fj;
             bloom[b] |= 1ull << (fj & 63);
             for (int j2 = 0; j2 < j; ++j2)
                 if (tok[(size_t)b * kMaxCons + off[(size_t)b * (kMaxCons + 1) + j2]] == fj)
@@ -419,6 +469,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->ws = static_cast<unsigned char *>(workspace_dev);
     c->L = L;
     c->stream = static_cast<hipStream_t>(hip_stream);
+    c->fused = env_int("DBA_FUSED", 1) ? 1 : 0;
     c->unroll = env_int("DBA_UNROLL", 4);
     c->waves = env_int("DBA_WAVES", 4);
     if (c->waves != 1 && c->waves != 2 && c->waves != 4) c->waves = 4;
@@ -433,15 +484,18 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     if (e == hipSuccess)
         e = hipMemcpyAsync(at<int32_t>(c, L.nphr), nph.data(), nph.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess)
+        e = hipMemcpyAsync(at<int32_t>(c, L.ftok), ftok.data(), ftok.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess)
         e = hipMemcpyAsync(at<u64>(c, L.sfl), sfl.data(), sfl.size() * 8, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess)
         e = hipMemcpyAsync(at<u64>(c, L.bloom), bloom.data(), bloom.size() * 8, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) {
-        dba_init_state_kernel<<<dim3((unsigned)B), dim3(kWave), 0, c->stream>>>(
-            B, k, at<int32_t>(c, L.cons_tok), at<int32_t>(c, L.phr_off), at<int32_t>(c, L.nphr),
-            at<float>(c, L.score[0]), at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]),
-            at<int32_t>(c, L.len[0]), at<uint8_t>(c, L.fin[0]), at<u64>(c, L.inc[0]),
-            at<int32_t>(c, L.nxt[0]), at<int32_t>(c, L.cwb[0]), at<unsigned int>(c, L.counters));
+        const int n = B * k;
+        dba_init_state_kernel<<<(n + 255) / 256, 256, 0, c->stream>>>(
+            B, k, at<int32_t>(c, L.phr_off), at<int32_t>(c, L.nphr), at<float>(c, L.score[0]),
+            at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]), at<int32_t>(c, L.len[0]),
+            at<uint8_t>(c, L.fin[0]), at<u64>(c, L.inc[0]), at<int32_t>(c, L.nxt[0]),
+            at<unsigned int>(c, L.counters));
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);   // host tables are freed on return
@@ -478,7 +532,6 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.fin_cur = at<uint8_t>(c, L.fin[cur]);
     p.inc_cur = at<u64>(c, L.inc[cur]);
     p.nxt_cur = at<int32_t>(c, L.nxt[cur]);
-    p.cwb_cur = at<int32_t>(c, L.cwb[cur]);
     p.score_nxt = at<float>(c, L.score[nxt]);
     p.met_nxt = at<u64>(c, L.met[nxt]);
     p.ipq_nxt = at<int32_t>(c, L.ipq[nxt]);
@@ -486,10 +539,10 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.fin_nxt = at<uint8_t>(c, L.fin[nxt]);
     p.inc_nxt = at<u64>(c, L.inc[nxt]);
     p.nxt_nxt = at<int32_t>(c, L.nxt[nxt]);
-    p.cwb_nxt = at<int32_t>(c, L.cwb[nxt]);
     p.cons_tok = at<int32_t>(c, L.cons_tok);
     p.phr_off = at<int32_t>(c, L.phr_off);
     p.nphr = at<int32_t>(c, L.nphr);
+    p.first_tok = at<int32_t>(c, L.ftok);
     p.same_first_lower = at<u64>(c, L.sfl);
     p.first_bloom = at<u64>(c, L.bloom);
     p.rowlists = at<u64>(c, L.rowlists);
@@ -503,13 +556,22 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.hist_token = at<int32_t>(c, L.hist_token) + hrow;
     p.hist_backptr = at<int32_t>(c, L.hist_backptr) + hrow;
 
-    const dim3 grid((unsigned)(c->B * c->k)), block((unsigned)(c->waves * kWave));
-    switch (c->unroll) {
-        case 2: dba_stream_kernel<2><<<grid, block, 0, c->stream>>>(p); break;
-        case 8: dba_stream_kernel<8><<<grid, block, 0, c->stream>>>(p); break;
-        default: dba_stream_kernel<4><<<grid, block, 0, c->stream>>>(p); break;
+    const dim3 grid((unsigned)(c->B * c->k));
+    if (c->fused) {
+        switch (c->unroll) {
+            case 2: dba_step_fused_kernel<2><<<grid, dim3(kBlock), c->dyn_smem, c->stream>>>(p); break;
+            case 8: dba_step_fused_kernel<8><<<grid, dim3(kBlock), c->dyn_smem, c->stream>>>(p); break;
+            default: dba_step_fused_kernel<4><<<grid, dim3(kBlock), c->dyn_smem, c->stream>>>(p); break;
+        }
+    } else {
+        const dim3 block((unsigned)(c->waves * kWave));
+        switch (c->unroll) {
+            case 2: dba_stream_kernel<2><<<grid, block, 0, c->stream>>>(p); break;
+            case 8: dba_stream_kernel<8><<<grid, block, 0, c->stream>>>(p); break;
+            default: dba_stream_kernel<4><<<grid, block, 0, c->stream>>>(p); break;
+        }
+        dba_merge_kernel<<<dim3((unsigned)c->B), dim3(kBlock), c->dyn_smem, c->stream>>>(p);
     }
-    dba_merge_kernel<<<dim3((unsigned)c->B), dim3(kBlock), c->dyn_smem, c->stream>>>(p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_step: launch failed: %s", hipGetErrorString(e));
     c->steps += 1;

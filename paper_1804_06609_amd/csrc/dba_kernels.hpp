@@ -5,12 +5,12 @@
 //                 log-probs of that row - score add, end-of-sentence mask,
 //                 exact top-k of the row (which holds the row's best token
 //                 and its share of the sentence's top-k) written as one sorted
-//                 64-key list per row - plus the gather of the row's
-//                 expandable constraint tokens (their sums, as selection keys);
+//                 64-key list per row - plus the row's expandable constraint
+//                 tokens (Alg. 2 inner loop): which they are, their sums, and the
+//                 bank each would land in, as selection keys;
 //   merge phase   one workgroup per sentence: sentence top-k from the row
 //                 lists, state transition add(), dedup, banks, allocation
-//                 with adjustment, selection, new beam, and the table of
-//                 tokens each new hypothesis may place at the next step.
+//                 with adjustment, selection, new beam.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <math.h>
@@ -41,8 +41,6 @@ struct StepParams {
     const uint8_t *fin_cur;           // [B,k]  kFin* flags
     const u64 *inc_cur;               // [B,k]  bit j = phrase j is not complete
     const int32_t *nxt_cur;           // [B,k]  next token of the phrase under way (-1: none)
-    const int32_t *cwb_cur;           // [B,k,64] phrase j: token the hypothesis may place now, with the
-                                      //          constraints met once it has (bank << 24 | token; -1: none)
     // beam after the step
     float *score_nxt;
     u64 *met_nxt;
@@ -51,11 +49,11 @@ struct StepParams {
     uint8_t *fin_nxt;
     u64 *inc_nxt;
     int32_t *nxt_nxt;
-    int32_t *cwb_nxt;
     // constraints
     const int32_t *cons_tok;          // [B,64]
     const int32_t *phr_off;           // [B,65] token offset of each phrase, phr_off[b][P] = C
     const int32_t *nphr;              // [B]
+    const int32_t *first_tok;         // [B,64] first token of phrase j
     const u64 *same_first_lower;      // [B,64] phrase j: the lower phrases with the same first token
     const u64 *first_bloom;           // [B] bit (w & 63) set for every phrase's first token w
     // scratch
@@ -82,19 +80,16 @@ struct MergeSmem {
     u64 sel[kMaxBeam];
     u64 met[kMaxBeam];                // beam before the step ...
     u64 inc[kMaxBeam];                // ... bit j = phrase j is not complete
-    u64 met2[kMaxBeam];               // beam after the step
     float prev[kMaxBeam];
     int ipq[kMaxBeam];
     int nmet[kMaxBeam];
     int nxt[kMaxBeam];                // next token of the phrase under way (-1: none under way)
-    int ipq2[kMaxBeam];
     int len[kMaxBeam];
     ConsTab ct;
     int cnt[kMaxCons + 1];
     int alloc[kMaxCons + 1];
     int start[kMaxCons + 1];
     unsigned char fin[kMaxBeam];
-    unsigned char fin2[kMaxBeam];
     int ncand;
     int nsel;
 };
@@ -365,65 +360,36 @@ __device__ __forceinline__ void RowStream<U>::run(float prev, int eos_block, uin
 // ---------------------------------------------------------------------------
 // constraint bookkeeping (Sec. 3.1): in-order phrases, one phrase under way
 // ---------------------------------------------------------------------------
-// Token that phrase j lets the hypothesis place now, or -1: the next token of
-// the phrase under way; the first token of a phrase neither complete nor under way.
-__device__ __forceinline__ int expandable_token(const ConsTab &sm, u64 met, int ip, int iq, int j)
+// Wave-wide, one lane per phrase: what the hypothesis (nmet tokens met, incomplete phrases inc,
+// phrase ip under way with iq tokens met and next token nxt) may place now (Alg. 2 inner loop,
+// Sec. 3.1 item 2) - the next token of the phrase under way, the first token of a phrase
+// neither complete nor under way.  Of equal tokens only the lowest phrase keeps its entry
+// (they are one coordinate).  Returns the lane's token or -1, and in bank the constraints met
+// once it is placed: nmet+1 if it continues the phrase under way or no phrase is under way,
+// else the phrase under way is unwound first (Sec. 3.1, last paragraph).
+// ftok = first token of the lane's phrase, sfl = lower phrases with the same first token.
+__device__ __forceinline__ int expandable_entry(int P, int nmet, u64 inc, int ip, int iq, int nxt, int ftok,
+                                                u64 sfl, int &bank)
 {
-    const int o = sm.poff[j];
-    if (j == ip) return sm.tok[o + iq];
-    const int last = sm.poff[j + 1] - 1;
-    if ((met >> last) & 1ull) return -1;
-    return sm.tok[o];
-}
-
-// State after emitting w: advance the phrase under way, or unwind it and let w
-// begin the lowest-index incomplete phrase that starts with w.
-__device__ __forceinline__ void cons_add(const ConsTab &sm, int P, u64 &met, int &ip, int &iq, int w)
-{
+    const int lane = lane_id();
+    const bool offers_first = lane < P && ((inc >> lane) & 1ull) && lane != ip;
+    const u64 F = __ballot(offers_first);
+    int w = -1;
+    if (lane == ip) w = nxt;
+    else if (offers_first && !(sfl & F)) w = ftok;
     if (ip >= 0) {
-        const int o = sm.poff[ip];
-        if (sm.tok[o + iq] == w) {
-            met |= 1ull << (o + iq);
-            ++iq;
-            if (o + iq == sm.poff[ip + 1]) {
-                ip = -1;
-                iq = 0;
+        const u64 E = __ballot(w >= 0 && lane != ip && w == nxt);   // at most one lane
+        if (E) {
+            const int lowest = __ffsll((long long)E) - 1;
+            if (lowest < ip) {
+                if (lane == ip) w = -1;
+            } else if (lane == lowest) {
+                w = -1;
             }
-            return;
         }
-        met &= ~(((1ull << iq) - 1ull) << o);
-        ip = -1;
-        iq = 0;
     }
-    for (int j = 0; j < P; ++j) {
-        const int o = sm.poff[j], e = sm.poff[j + 1];
-        if ((met >> (e - 1)) & 1ull) continue;
-        if (sm.tok[o] != w) continue;
-        met |= 1ull << o;
-        if (e - o > 1) {
-            ip = j;
-            iq = 1;
-        }
-        return;
-    }
-}
-
-// Entry j of the table a hypothesis carries into the next step: the token phrase j lets it
-// place (-1 if none, or if a lower phrase offers the same token - the candidate would be the
-// same coordinate) and the number of constraints met once it has placed it.
-__device__ __forceinline__ void next_token_entry(const ConsTab &ct, int P, u64 met, int ip, int iq,
-                                                 int j, int &w, int &bank)
-{
-    w = j < P ? expandable_token(ct, met, ip, iq, j) : -1;
-    for (int j2 = 0; j2 < j && w >= 0; ++j2)
-        if (expandable_token(ct, met, ip, iq, j2) == w) w = -1;
-    bank = 0;
-    if (w >= 0) {
-        u64 m2 = met;
-        int ip2 = ip, iq2 = iq;
-        cons_add(ct, P, m2, ip2, iq2, w);
-        bank = __popcll(m2);
-    }
+    bank = (ip < 0 || lane == ip || w == nxt) ? nmet + 1 : nmet - iq + 1;
+    return w;
 }
 
 // ---------------------------------------------------------------------------
@@ -543,6 +509,9 @@ __device__ __forceinline__ int nmet_after(int nmet, int ip, int iq, bool is_next
     return base + ((match & inc) ? 1 : 0);
 }
 
+// COHERENT: the row lists were written by other workgroups of the same launch and are read
+// with device-scope atomic loads (see dba_step_fused_kernel).
+template <bool COHERENT>
 __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSmem &sm, u64 *cand)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
@@ -560,7 +529,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const size_t rs = (size_t)b * k + hs;
     const int ld_poff = p.phr_off[(size_t)b * (kMaxCons + 1) + t64];
     const int ld_tok = p.cons_tok[(size_t)b * kMaxCons + lane];
-    const u64 sfl = p.same_first_lower[(size_t)b * kMaxCons + lane];
+    const int ftok = p.first_tok[(size_t)b * kMaxCons + lane];   // first token of this lane's phrase, -1 beyond P
     const int P = p.nphr[b];
     const u64 bloom = p.first_bloom[b];
     const float ld_prev = p.score_cur[rs];
@@ -578,8 +547,14 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         rl[i] = 0;
         ck[i] = 0;
         if (h < k) {
-            rl[i] = p.rowlists[((size_t)b * k + h) * kWave + lane];
-            ck[i] = p.conskeys[((size_t)b * k + h) * kWave + lane];
+            const size_t o = ((size_t)b * k + h) * kWave + lane;
+            if (COHERENT) {
+                rl[i] = __hip_atomic_load(p.rowlists + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ck[i] = __hip_atomic_load(p.conskeys + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                rl[i] = p.rowlists[o];
+                ck[i] = p.conskeys[o];
+            }
         }
     }
     if (tid <= kMaxCons) {
@@ -618,11 +593,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     sm.wl[wave][lane] = acc;
     __syncthreads();                                   // tables, beam and partial lists are in LDS
 
-    // this lane's phrase (lane < P): token range [po, pe) and first token
     const int C = sm.ct.poff[P];
-    const int po = lane < P ? sm.ct.poff[lane] : 0;
-    const int pe = lane < P ? sm.ct.poff[lane + 1] : 1;
-    const int ftok = lane < P ? sm.ct.tok[po] : -1;
     for (int w = 1; w < kWavesPerBlock; ++w) {
         const u64 other = sm.wl[(wave + w) & (kWavesPerBlock - 1)][lane];
         if (read_lane(other, 0) > read_lane(acc, k - 1)) acc = merge_desc<u64>(acc, other);
@@ -760,9 +731,9 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const int nsel = sm.nsel;
     if (wave == 0) {
         const u64 mine = sort64_desc<u64>(lane < nsel ? sm.sel[lane] : 0ull);   // lane = new slot
-        int token = p.pad_id, parent = -1, length = 0, ipq2 = -1;
+        int token = p.pad_id, parent = -1, length = 0, ipq2 = -1, nxt2 = -1;
         float score = -INFINITY;
-        u64 met2 = 0;
+        u64 met2 = 0, inc2 = 0;
         uint8_t flags = 2, fin2 = 0;
         const bool live = lane < nsel;
         if (live) {
@@ -774,6 +745,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         const u64 match = first_token_matches(live ? token : -1, ftok, P, bloom);
         if (live) {
             met2 = sm.met[parent];
+            inc2 = sm.inc[parent];
             const int ipq = sm.ipq[parent];
             int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
             const bool pfin = sm.fin[parent] != 0;
@@ -785,6 +757,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
                     met2 |= 1ull << (o + iq);
                     ++iq;
                     if (o + iq == sm.ct.poff[ip + 1]) {
+                        inc2 &= ~(1ull << ip);
                         ip = -1;
                         iq = 0;
                     }
@@ -802,23 +775,25 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
                         if (sm.ct.poff[j + 1] - o > 1) {
                             ip = j;
                             iq = 1;
+                        } else {
+                            inc2 &= ~(1ull << j);
                         }
                     }
                 }
             }
             ipq2 = ip < 0 ? -1 : ((ip << 8) | iq);
+            nxt2 = ip < 0 ? -1 : sm.ct.tok[sm.ct.poff[ip] + iq];
             fin2 = (pfin || token == p.eos_id) ? 1 : 0;
             length = pfin ? sm.len[parent] : sm.len[parent] + 1;
             flags = fin2;
         }
         if (lane < k) {
-            sm.met2[lane] = met2;
-            sm.ipq2[lane] = ipq2;
-            sm.fin2[lane] = (uint8_t)(fin2 | (live ? 0 : 2));
             const size_t o = (size_t)b * k + lane;
             p.score_nxt[o] = score;
             p.met_nxt[o] = met2;
+            p.inc_nxt[o] = inc2;
             p.ipq_nxt[o] = ipq2;
+            p.nxt_nxt[o] = nxt2;
             p.len_nxt[o] = length;
             p.fin_nxt[o] = (uint8_t)(fin2 | ((live && !fin2 && __popcll(met2) < C) ? kFinEosBlocked : 0));
             p.hist_token[o] = token;
@@ -827,48 +802,6 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             if (p.out_backptr) p.out_backptr[o] = parent;
             if (p.out_score) p.out_score[o] = score;
             if (p.out_flags) p.out_flags[o] = flags;
-        }
-    }
-    __syncthreads();
-
-    // ---- what every new hypothesis may place at the next step (Alg. 2 inner loop), one wave
-    // per hypothesis, one lane per phrase: the next token of the phrase under way, the first
-    // token of a phrase neither complete nor under way; of equal tokens only the lowest phrase
-    // keeps its entry (same coordinate); with it the constraints met once it is placed ------
-    for (int slot = wave; slot < k; slot += kWavesPerBlock) {
-        int w = -1, bank = 0, nxt2 = -1;
-        u64 inc2 = 0;
-        if (sm.fin2[slot] == 0) {                          // live and unfinished (wave-uniform)
-            const u64 met2 = sm.met2[slot];
-            const int ipq = sm.ipq2[slot];
-            const int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
-            const int nm = __popcll(met2);
-            nxt2 = ip < 0 ? -1 : sm.ct.tok[sm.ct.poff[ip] + iq];
-            const bool incomplete = lane < P && !((met2 >> (pe - 1)) & 1ull);
-            inc2 = __ballot(incomplete);
-            const bool offers_first = incomplete && lane != ip;
-            const u64 F = __ballot(offers_first);
-            if (lane == ip) w = nxt2;
-            else if (offers_first && !(sfl & F)) w = ftok;
-            if (ip >= 0) {
-                const u64 E = __ballot(w >= 0 && lane != ip && w == nxt2);   // at most one lane
-                if (E) {
-                    const int lowest = __ffsll((long long)E) - 1;
-                    if (lowest < ip) {
-                        if (lane == ip) w = -1;
-                    } else if (lane == lowest) {
-                        w = -1;
-                    }
-                }
-            }
-            if (w >= 0) bank = (ip < 0 || lane == ip || w == nxt2) ? nm + 1 : nm - iq + 1;
-        } else if (sm.fin2[slot] == 1) {
-            inc2 = 0;
-        }
-        p.cwb_nxt[((size_t)b * k + slot) * kMaxCons + lane] = w >= 0 ? ((bank << 24) | w) : -1;
-        if (lane == 0) {
-            p.inc_nxt[(size_t)b * k + slot] = inc2;
-            p.nxt_nxt[(size_t)b * k + slot] = nxt2;
         }
     }
 }
