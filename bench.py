@@ -11,8 +11,10 @@ initialised before the timed region).  Inputs rotate over several distinct resid
 that the 164 MB per step cannot be served from the 256 MB Infinity Cache.
 
 Prints ONE JSON line.  `value` = steps/s (wall clock, synchronised on both sides);
-`roofline.achieved` = algorithmic bytes per launch / average launch duration measured with
-HIP events on the launch stream; `cpu_baseline` = the CPU oracle timed on this machine's cores.
+`roofline.achieved` = algorithmic bytes per launch / average launch duration of the step
+kernel (one launch per step: stream phase and merge phase are fused), measured with HIP events
+on the launch stream over the timed region; `cpu_baseline` = the CPU oracle timed on this
+box's cores.
 """
 from __future__ import annotations
 
@@ -146,7 +148,9 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": None,
-            "kernel": "dba_step_kernel (fused stream+merge, one launch per step)",
+            "kernel": "dba_step_fused_kernel<4> (one launch per step: stream phase + merge phase)"
+                      if os.environ.get("DBA_FUSED", "1") != "0" else
+                      "dba_stream_kernel<4> + dba_merge_kernel (two launches per step; figure is per step)",
             "us_per_launch": ev_ms * 1e3 / launches,
             "algorithmic_bytes_per_launch": bytes_total / launches,
         },

@@ -587,7 +587,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         if (h < k) {                                   // wave-uniform
             if (lane == 0) sm.rb[h] = body_from_rowkey(mb, rl[i]);
             if (i == 0) acc = rl[0];
-            else if (read_lane(rl[i], 0) > read_lane(acc, k - 1)) acc = merge_desc<u64>(acc, rl[i]);
+            else if (read_lane(rl[i], 0) > read_lane(acc, k - 1)) acc = merge_desc<u64, true>(acc, rl[i]);
         }
     }
     sm.wl[wave][lane] = acc;
@@ -596,7 +596,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const int C = sm.ct.poff[P];
     for (int w = 1; w < kWavesPerBlock; ++w) {
         const u64 other = sm.wl[(wave + w) & (kWavesPerBlock - 1)][lane];
-        if (read_lane(other, 0) > read_lane(acc, k - 1)) acc = merge_desc<u64>(acc, other);
+        if (read_lane(other, 0) > read_lane(acc, k - 1)) acc = merge_desc<u64, true>(acc, other);
     }
     // every wave now holds the sentence's best keys, lane i = i-th best.
     // tau = k-th best; 0 while fewer than k finite sums exist, in which case every finite sum
@@ -691,7 +691,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const int my_first = kWavesPerBlock - 1 - wave;
     for (int c = my_first; c < nchunks; c += kWavesPerBlock) {
         const int i = c * kWave + lane;
-        cand[i] = sort64_desc<u64>(i < ncand ? cand[i] : 0ull);
+        cand[i] = sort64_desc<u64, true>(i < ncand ? cand[i] : 0ull);
     }
     __syncthreads();
     for (int c = my_first; c < nchunks; c += kWavesPerBlock) {
@@ -730,7 +730,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     // ---- new beam, best first (Sec. 3.1); empty slots last ---------------------------------
     const int nsel = sm.nsel;
     if (wave == 0) {
-        const u64 mine = sort64_desc<u64>(lane < nsel ? sm.sel[lane] : 0ull);   // lane = new slot
+        const u64 mine = sort64_desc<u64, true>(lane < nsel ? sm.sel[lane] : 0ull);   // lane = new slot
         int token = p.pad_id, parent = -1, length = 0, ipq2 = -1, nxt2 = -1;
         float score = -INFINITY;
         u64 met2 = 0, inc2 = 0;

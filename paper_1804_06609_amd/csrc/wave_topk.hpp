@@ -84,106 +84,110 @@ __device__ __forceinline__ uint32_t xor32_u32(uint32_t v)
     return (lane_id() & 32) ? r[0] : r[1];
 }
 
+// value held by lane (lane ^ 16): rows of 16 lanes are exchanged pairwise
+__device__ __forceinline__ uint32_t xor16_valu_u32(uint32_t v)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return (lane_id() & 16) ? r[0] : r[1];
+}
+
+// Two flavours of every exchange.  LL = false: the fewest VALU instructions (ds_swizzle does
+// the move outside the VALU) - for code that competes for the VALU with other waves.
+// LL = true: the shortest latency (DPP / permlane only, no trip through the LDS crossbar) -
+// for code whose waves run alone and wait on every step.
 // value held by lane (lane ^ J), J a power of two
-template <int J>
+template <int J, bool LL>
 __device__ __forceinline__ uint32_t xor_lane_u32(uint32_t v)
 {
     if constexpr (J == 1) return dpp_mov<kDppXor1>(v);
     else if constexpr (J == 2) return dpp_mov<kDppXor2>(v);
     else if constexpr (J == 32) return xor32_u32(v);
-    else return swizzle_xor_u32<J>(v);
+    else if constexpr (!LL) return swizzle_xor_u32<J>(v);
+    else if constexpr (J == 4) return dpp_mov<kDppQuadRev>(dpp_mov<kDppHalfMirror>(v));
+    else if constexpr (J == 8) return dpp_mov<kDppHalfMirror>(dpp_mov<kDppRowMirror>(v));
+    else return xor16_valu_u32(v);
 }
 
 // value held by the mirror lane inside blocks of S lanes: lane ^ (S-1)
-template <int S>
+template <int S, bool LL>
 __device__ __forceinline__ uint32_t flip_lane_u32(uint32_t v)
 {
     if constexpr (S == 2) return dpp_mov<kDppXor1>(v);
     else if constexpr (S == 4) return dpp_mov<kDppQuadRev>(v);
     else if constexpr (S == 8) return dpp_mov<kDppHalfMirror>(v);
     else if constexpr (S == 16) return dpp_mov<kDppRowMirror>(v);
-    else if constexpr (S == 32) return swizzle_xor_u32<31>(v);
-    else return swizzle_xor_u32<31>(xor32_u32(v));
-}
-
-template <int J>
-__device__ __forceinline__ u64 xor_lane(u64 v)
-{
-    return ((u64)xor_lane_u32<J>((uint32_t)(v >> 32)) << 32) | xor_lane_u32<J>((uint32_t)v);
-}
-
-template <int S>
-__device__ __forceinline__ u64 flip_lane(u64 v)
-{
-    return ((u64)flip_lane_u32<S>((uint32_t)(v >> 32)) << 32) | flip_lane_u32<S>((uint32_t)v);
+    else if constexpr (S == 32) return LL ? dpp_mov<kDppRowMirror>(xor16_valu_u32(v)) : swizzle_xor_u32<31>(v);
+    else return LL ? dpp_mov<kDppRowMirror>(xor16_valu_u32(xor32_u32(v))) : swizzle_xor_u32<31>(xor32_u32(v));
 }
 
 // ---- compare-exchange networks (T = u64 keys or u32 order-preserving images) ---------
-template <typename T, int J>
+template <typename T, int J, bool LL>
 __device__ __forceinline__ T xor_lane_t(T v)
 {
-    if constexpr (sizeof(T) == 8) return xor_lane<J>(v);
-    else return xor_lane_u32<J>(v);
+    if constexpr (sizeof(T) == 8)
+        return ((u64)xor_lane_u32<J, LL>((uint32_t)(v >> 32)) << 32) | xor_lane_u32<J, LL>((uint32_t)v);
+    else return xor_lane_u32<J, LL>(v);
 }
 
-template <typename T, int S>
+template <typename T, int S, bool LL>
 __device__ __forceinline__ T flip_lane_t(T v)
 {
-    if constexpr (sizeof(T) == 8) return flip_lane<S>(v);
-    else return flip_lane_u32<S>(v);
+    if constexpr (sizeof(T) == 8)
+        return ((u64)flip_lane_u32<S, LL>((uint32_t)(v >> 32)) << 32) | flip_lane_u32<S, LL>((uint32_t)v);
+    else return flip_lane_u32<S, LL>(v);
 }
 
 // half-cleaner at distance J: the lower lane of each pair keeps the greater value
-template <typename T, int J>
+template <typename T, int J, bool LL>
 __device__ __forceinline__ T clean_desc(T v)
 {
-    const T other = xor_lane_t<T, J>(v);
+    const T other = xor_lane_t<T, J, LL>(v);
     const bool upper = (lane_id() & J) != 0;
     return ((v < other) != upper) ? other : v;
 }
 
 // sorts a bitonic run inside every block of S lanes, decreasing
-template <typename T, int S>
+template <typename T, int S, bool LL>
 __device__ __forceinline__ T bitonic_finish_desc(T v)
 {
-    if constexpr (S >= 64) v = clean_desc<T, 32>(v);
-    if constexpr (S >= 32) v = clean_desc<T, 16>(v);
-    if constexpr (S >= 16) v = clean_desc<T, 8>(v);
-    if constexpr (S >= 8) v = clean_desc<T, 4>(v);
-    if constexpr (S >= 4) v = clean_desc<T, 2>(v);
-    if constexpr (S >= 2) v = clean_desc<T, 1>(v);
+    if constexpr (S >= 64) v = clean_desc<T, 32, LL>(v);
+    if constexpr (S >= 32) v = clean_desc<T, 16, LL>(v);
+    if constexpr (S >= 16) v = clean_desc<T, 8, LL>(v);
+    if constexpr (S >= 8) v = clean_desc<T, 4, LL>(v);
+    if constexpr (S >= 4) v = clean_desc<T, 2, LL>(v);
+    if constexpr (S >= 2) v = clean_desc<T, 1, LL>(v);
     return v;
 }
 
 // merges the two decreasing halves of every block of S lanes into one decreasing block
-template <typename T, int S>
+template <typename T, int S, bool LL>
 __device__ __forceinline__ T merge_halves_desc(T v)
 {
-    const T other = flip_lane_t<T, S>(v);
+    const T other = flip_lane_t<T, S, LL>(v);
     const bool upper = (lane_id() & (S >> 1)) != 0;
     v = ((v < other) != upper) ? other : v;
-    return bitonic_finish_desc<T, (S >> 1)>(v);
+    return bitonic_finish_desc<T, (S >> 1), LL>(v);
 }
 
 // Full sort of one value per lane, decreasing by lane.
-template <typename T>
+template <typename T, bool LL = false>
 __device__ __forceinline__ T sort64_desc(T v)
 {
-    v = merge_halves_desc<T, 2>(v);
-    v = merge_halves_desc<T, 4>(v);
-    v = merge_halves_desc<T, 8>(v);
-    v = merge_halves_desc<T, 16>(v);
-    v = merge_halves_desc<T, 32>(v);
-    v = merge_halves_desc<T, 64>(v);
+    v = merge_halves_desc<T, 2, LL>(v);
+    v = merge_halves_desc<T, 4, LL>(v);
+    v = merge_halves_desc<T, 8, LL>(v);
+    v = merge_halves_desc<T, 16, LL>(v);
+    v = merge_halves_desc<T, 32, LL>(v);
+    v = merge_halves_desc<T, 64, LL>(v);
     return v;
 }
 
 // a, b: decreasing lists.  Returns the 64 greatest of their union, decreasing.
-template <typename T>
+template <typename T, bool LL = false>
 __device__ __forceinline__ T merge_desc(T a, T b)
 {
-    const T b_rev = flip_lane_t<T, 64>(b);
-    return bitonic_finish_desc<T, 64>(a > b_rev ? a : b_rev);   // bitonic, holds the top 64
+    const T b_rev = flip_lane_t<T, 64, LL>(b);
+    return bitonic_finish_desc<T, 64, LL>(a > b_rev ? a : b_rev);   // bitonic, holds the top 64
 }
 
 // Insert the wave-uniform key x (x != 0, not already present) into a decreasing list;

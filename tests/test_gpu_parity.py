@@ -150,7 +150,7 @@ def test_config5(torch_gpu):
     """Full shape (B=128, k=64, V=50000).  The oracle follows a sample of sentences through
     every step (its cost per sentence-step is ~0.3 s); all sentences are checked against the
     properties that hold at any size.  DBA_TEST_CONFIG5_STEPS overrides the step count."""
-    T = int(os.environ.get("DBA_TEST_CONFIG5_STEPS", "40"))
+    T = int(os.environ.get("DBA_TEST_CONFIG5_STEPS", "120"))
     wl = si.make_config(5, T=T)
     ntok = [wl.n_tokens(b) for b in range(wl.B)]
     sample = sorted({int(np.argmin(ntok)), int(np.argmax(ntok)), 0, 1, 63, 64, 126, 127})
