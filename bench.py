@@ -30,6 +30,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+# HBM bytes per launch (fetched + written) of the step kernel on the config-4 workload, from the
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled against a plain copy);
+# None whenever the kernel has changed since those counters were taken.
+TRAFFIC_BYTES_PER_LAUNCH = None
 
 
 def build_workload(cfg: int, cons_tokens):
@@ -53,6 +57,9 @@ def main():
     ap.add_argument("--decode-len", type=int, default=None, help="steps per decode (default: the config's)")
     ap.add_argument("--repeats", type=int, default=5, help="timed repetitions; the median is reported")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain device copy of one input tensor (known size) a few times, so "
+                         "that a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; sentences shard across GPUs without any "
@@ -147,7 +154,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": TRAFFIC_BYTES_PER_LAUNCH if (args.config == 4 and args.cons_tokens is None) else None,
             "kernel": "dba_step_fused_kernel<4> (one launch per step: stream phase + merge phase)"
                       if os.environ.get("DBA_FUSED", "1") != "0" else
                       "dba_stream_kernel<4> + dba_merge_kernel (two launches per step; figure is per step)",
@@ -155,6 +162,13 @@ def main():
             "algorithmic_bytes_per_launch": bytes_total / launches,
         },
     }
+
+    if args.copy_probe:
+        dst = torch.empty_like(dev[0])
+        for i in range(4):
+            dst.copy_(dev[i % R])        # reads 4*B*k*V bytes, writes as many
+        torch.cuda.synchronize()
+        out["copy_probe_bytes_each_way"] = 4 * B * k * V
 
     if not args.no_cpu_baseline:
         import oracle

@@ -48,7 +48,8 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
     }
     const float *__restrict__ logp_row = p.logp + (size_t)row * (size_t)p.V;
     RowStream<U> rs;
-    rs.begin(logp_row, p.V, wave, nwaves);
+    const bool known_empty = p.first_step && h != 0;   // decoder-init leaves slots 1.. empty
+    if (!known_empty) rs.begin(logp_row, p.V, wave, nwaves);
     if (threadIdx.x == 0) sm.thr = ord_from_float(-INFINITY);
 
     // the row's hypothesis: wave-uniform by construction, made so for the compiler
@@ -62,7 +63,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
     st.floor = -INFINITY;
     st.thr = kLowestFinite;
     u64 ckey = 0;
-    if (prev > -INFINITY && !(fin & kFinFinished)) {
+    if (prev > -INFINITY && !(fin & kFinFinished) && !known_empty) {
         // Alg. 2 inner loop / Sec. 3.1 item 2: the hypothesis extended by each constraint token
         // it may place now; the log-prob is one 4-byte read per token, in flight during the stream
         int cw = -1, cbank = 0;
@@ -524,6 +525,7 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.eos_id = c->eos_id; p.pad_id = c->pad_id;
     p.met_bits = c->met_bits;
     p.tok_bits = c->tok_bits;
+    p.first_step = c->steps == 0 ? 1 : 0;
     p.logp = logp_dev;
     p.score_cur = at<float>(c, L.score[cur]);
     p.met_cur = at<u64>(c, L.met[cur]);

@@ -32,6 +32,7 @@ struct StepParams {
     int eos_id, pad_id;
     int met_bits;                     // width of the bank field in the packed selection key
     int tok_bits;                     // width of the token field of a coordinate: (h << tok_bits) | w
+    int first_step;                   // 1: the beam is the initial one (only slot 0 of a sentence is live)
     const float *logp;                // [B,k,V]
     // beam before the step
     const float *score_cur;           // [B,k]  (-inf: empty slot)
