@@ -45,6 +45,57 @@ def build_workload(cfg: int, cons_tokens):
     return wl
 
 
+def timed_steps(wl, dev, K, W, dlen, repeats):
+    """Median wall seconds and event milliseconds of K steps (fresh contexts every repeat)."""
+    import torch
+    from paper_1804_06609_amd.session import Session
+    toks, poff, soff = wl.csr()
+    R = len(dev)
+    stream = torch.cuda.current_stream()
+    wall, evms = [], []
+    for _ in range(repeats):
+        n_dec = (W + K + dlen - 1) // dlen
+        sessions = [Session(wl.B, wl.k, wl.V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff) for _ in range(n_dec)]
+        g = 0
+        for _ in range(W):
+            sessions[g // dlen].step(dev[g % R])
+            g += 1
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(K):
+            sessions[g // dlen].step(dev[g % R])
+            g += 1
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall.append(time.perf_counter() - t0)
+        evms.append(e0.elapsed_time(e1))
+        for s in sessions:
+            s.close()
+    return float(np.median(wall)), float(np.median(evms))
+
+
+def flatness(args):
+    """Sec. 1 / Table 1: the cost of a DBA step does not grow with the number of constraints."""
+    import torch
+    torch.cuda.set_device(0)
+    res = {}
+    dev = None
+    for c in (1, 2, 4, 8, 16, 32):
+        wl = build_workload(args.config, c)
+        if dev is None:           # the log-probs do not depend on the constraints
+            dev = [torch.from_numpy(wl.logp(t)).cuda() for t in range(max(1, args.tensors))]
+        wall_s, _ = timed_steps(wl, dev, args.steps, args.warmup, args.decode_len or wl.T, max(3, args.repeats))
+        res[str(c)] = wall_s * 1e3 / args.steps
+    vals = list(res.values())
+    print(json.dumps({"metric": "DBA ms/step vs constraint tokens per sentence", "unit": "ms",
+                      "config": {"workload": f"config{args.config} shapes, exactly C constraint tokens per sentence"},
+                      "ms_per_step": res, "max_over_min": max(vals) / min(vals), "steps": args.steps,
+                      "warmup": args.warmup, "n_gpus": 1, "data": "synthetic"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,6 +108,9 @@ def main():
     ap.add_argument("--decode-len", type=int, default=None, help="steps per decode (default: the config's)")
     ap.add_argument("--repeats", type=int, default=5, help="timed repetitions; the median is reported")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--flatness", action="store_true",
+                    help="instead of the headline line: step time for 1,2,4,8,16,32 constraint tokens per "
+                         "sentence (the paper's O(1)-in-C claim), one JSON line")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain device copy of one input tensor (known size) a few times, so "
                          "that a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -76,6 +130,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    if args.flatness:
+        return flatness(args)
+
     wl = build_workload(args.config, args.cons_tokens)
     B, k, V = wl.B, wl.k, wl.V
     K, W, R = args.steps, args.warmup, max(1, args.tensors)
@@ -87,36 +144,7 @@ def main():
     dev = [torch.from_numpy(h).cuda() for h in host]
     torch.cuda.synchronize()
 
-    def run(nsteps_total):
-        """Fresh contexts, then nsteps_total steps as back-to-back decodes of dlen steps."""
-        n_dec = (nsteps_total + dlen - 1) // dlen
-        return [Session(B, k, V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff) for _ in range(n_dec)]
-
-    stream = torch.cuda.current_stream()
-    wall, evms = [], []
-    for rep in range(args.repeats):
-        sessions = run(W + K)
-        g = 0
-        for _ in range(W):
-            sessions[g // dlen].step(dev[g % R])
-            g += 1
-        torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record(stream)
-        for _ in range(K):
-            sessions[g // dlen].step(dev[g % R])
-            g += 1
-        e1.record(stream)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        wall.append(t1 - t0)
-        evms.append(e0.elapsed_time(e1))
-        for s in sessions:
-            s.close()
-    wall_s = float(np.median(wall))
-    ev_ms = float(np.median(evms))
+    wall_s, ev_ms = timed_steps(wl, dev, K, W, dlen, args.repeats)
 
     # algorithmic bytes: every live row's V log-probs once.  The first step of a decode has one
     # live row, all later steps k (EOS never fires in this workload).
