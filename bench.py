@@ -11,10 +11,11 @@ initialised before the timed region).  Inputs rotate over several distinct resid
 that the 164 MB per step cannot be served from the 256 MB Infinity Cache.
 
 Prints ONE JSON line.  `value` = steps/s (wall clock, synchronised on both sides);
-`roofline.achieved` = algorithmic bytes per launch / average launch duration of the step
-kernel (one launch per step: stream phase and merge phase are fused), measured with HIP events
-on the launch stream over the timed region; `cpu_baseline` = the CPU oracle timed on this
-box's cores.
+`roofline.achieved` = algorithmic bytes per step / average duration of one step's launches
+(dba_stream_kernel, which reads the log-probs, followed by dba_merge_kernel), measured with HIP
+events on the launch stream over the timed region - the two kernels run back to back with no
+gap, so this is the sum of their durations; profiles/ holds the rocprofv3 split of the two.
+`cpu_baseline` = the CPU oracle timed on this machine's cores.
 """
 from __future__ import annotations
 
@@ -183,9 +184,9 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": TRAFFIC_BYTES_PER_LAUNCH if (args.config == 4 and args.cons_tokens is None) else None,
-            "kernel": "dba_step_fused_kernel<4> (one launch per step: stream phase + merge phase)"
-                      if os.environ.get("DBA_FUSED", "1") != "0" else
-                      "dba_stream_kernel<4> + dba_merge_kernel (two launches per step; figure is per step)",
+            "kernel": "dba_stream_kernel<4> + dba_merge_kernel (the two launches of one step, back to back)"
+                      if os.environ.get("DBA_FUSED", "0") == "0" else
+                      "dba_step_fused_kernel<4> (one launch per step: stream phase + merge phase)",
             "us_per_launch": ev_ms * 1e3 / launches,
             "algorithmic_bytes_per_launch": bytes_total / launches,
         },

@@ -93,7 +93,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
     }
     if (wave == 0) {
         u64 acc = st.list;
-        for (int w = 1; w < nwaves; ++w) acc = merge_desc<u64>(acc, sm.wl[w][lane]);
+        for (int w = 1; w < nwaves; ++w) acc = merge_desc<u64, true>(acc, sm.wl[w][lane]);
         u64 *dst = p.rowlists + (size_t)row * kWave + lane;
         if (PUBLISH) __hip_atomic_store(dst, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else *dst = acc;
@@ -470,7 +470,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->ws = static_cast<unsigned char *>(workspace_dev);
     c->L = L;
     c->stream = static_cast<hipStream_t>(hip_stream);
-    c->fused = env_int("DBA_FUSED", 1) ? 1 : 0;
+    c->fused = env_int("DBA_FUSED", 0) ? 1 : 0;
     c->unroll = env_int("DBA_UNROLL", 4);
     c->waves = env_int("DBA_WAVES", 4);
     if (c->waves != 1 && c->waves != 2 && c->waves != 4) c->waves = 4;

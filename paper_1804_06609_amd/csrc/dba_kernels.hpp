@@ -139,6 +139,18 @@ __device__ __attribute__((noinline)) u64 fold_stage(u64 list, const u64 *stage, 
     return list;
 }
 
+// The same at the end of the row, when nothing is left to overlap with: shortest latency.
+__device__ __forceinline__ u64 fold_stage_last(u64 list, const u64 *stage, int cnt)
+{
+    const int lane = lane_id();
+    for (int base = 0; base < cnt; base += kWave) {
+        const u64 key = (base + lane < cnt) ? stage[base + lane] : 0ull;
+        const u64 sorted = sort64_desc<u64, true>(key);
+        list = (base == 0 && list == 0) ? sorted : merge_desc<u64, true>(list, sorted);
+    }
+    return list;
+}
+
 __device__ __forceinline__ void flush_stage(RowTop &st, u64 *stage, int &cnt, int kk)
 {
     st.list = fold_stage(st.list, stage, cnt);
@@ -277,6 +289,7 @@ __device__ __forceinline__ void RowStream<U>::run(float prev, int eos_block, uin
     int tl = wave;
     uint32_t boot = ord_from_float(-INFINITY);
     if (tl < ntiles) {
+        // both tiles already requested take part in the floor (8 KB per wave, 32 KB per row)
         const int rel = eos_rel0 - tl * (4 * kWave * U);
         if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(cur, rel, lane);
         float lane_max = max4(cur[0]);
@@ -284,6 +297,15 @@ __device__ __forceinline__ void RowStream<U>::run(float prev, int eos_block, uin
         for (int u = 1; u < U; ++u) {
             const float mu = max4(cur[u]);
             asm("v_max_f32 %0, %1, %2" : "=v"(lane_max) : "v"(lane_max), "v"(mu));
+        }
+        if (tl + nwaves < ntiles) {
+            const int rel2 = eos_rel0 - (tl + nwaves) * (4 * kWave * U);
+            if (eos_rel0 >= 0 && rel2 >= 0 && rel2 < 4 * kWave * U) block_eos<U>(nxt, rel2, lane);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float mu = max4(nxt[u]);
+                asm("v_max_f32 %0, %1, %2" : "=v"(lane_max) : "v"(lane_max), "v"(mu));
+            }
         }
         boot = sort64_desc<uint32_t>(ord_from_float(prev + lane_max));
     }
@@ -355,7 +377,7 @@ __device__ __forceinline__ void RowStream<U>::run(float prev, int eos_block, uin
             cnt += 1;
         }
     }
-    if (cnt > 0) flush_stage(st, stage, cnt, kk);
+    if (cnt > 0) st.list = fold_stage_last(st.list, stage, cnt);
 }
 
 // ---------------------------------------------------------------------------
