@@ -46,7 +46,7 @@ def build_workload(cfg: int, cons_tokens):
     return wl
 
 
-def timed_steps(wl, dev, K, W, dlen, repeats):
+def timed_steps(wl, dev, K, W, dlen, repeats, options=None):
     """Median wall seconds and event milliseconds of K steps (fresh contexts every repeat)."""
     import torch
     from paper_1804_06609_amd.session import Session
@@ -56,7 +56,8 @@ def timed_steps(wl, dev, K, W, dlen, repeats):
     wall, evms = [], []
     for _ in range(repeats):
         n_dec = (W + K + dlen - 1) // dlen
-        sessions = [Session(wl.B, wl.k, wl.V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff) for _ in range(n_dec)]
+        sessions = [Session(wl.B, wl.k, wl.V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff, options=options)
+                    for _ in range(n_dec)]
         g = 0
         for _ in range(W):
             sessions[g // dlen].step(dev[g % R])
@@ -112,6 +113,8 @@ def main():
     ap.add_argument("--flatness", action="store_true",
                     help="instead of the headline line: step time for 1,2,4,8,16,32 constraint tokens per "
                          "sentence (the paper's O(1)-in-C claim), one JSON line")
+    ap.add_argument("--fused", action="store_true",
+                    help="time the one-launch form of the step (DBA_OPT_FUSED_LAUNCH) instead of the default")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain device copy of one input tensor (known size) a few times, so "
                          "that a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -145,7 +148,9 @@ def main():
     dev = [torch.from_numpy(h).cuda() for h in host]
     torch.cuda.synchronize()
 
-    wall_s, ev_ms = timed_steps(wl, dev, K, W, dlen, args.repeats)
+    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
+    options = {DBA_OPT_FUSED_LAUNCH: 1} if args.fused else None
+    wall_s, ev_ms = timed_steps(wl, dev, K, W, dlen, args.repeats, options)
 
     # algorithmic bytes: every live row's V log-probs once.  The first step of a decode has one
     # live row, all later steps k (EOS never fires in this workload).
@@ -183,9 +188,10 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": TRAFFIC_BYTES_PER_LAUNCH if (args.config == 4 and args.cons_tokens is None) else None,
+            "traffic": TRAFFIC_BYTES_PER_LAUNCH
+            if (args.config == 4 and args.cons_tokens is None and not args.fused) else None,
             "kernel": "dba_stream_kernel<4> + dba_merge_kernel (the two launches of one step, back to back)"
-                      if os.environ.get("DBA_FUSED", "0") == "0" else
+                      if not args.fused else
                       "dba_step_fused_kernel<4> (one launch per step: stream phase + merge phase)",
             "us_per_launch": ev_ms * 1e3 / launches,
             "algorithmic_bytes_per_launch": bytes_total / launches,

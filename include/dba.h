@@ -138,6 +138,17 @@ DBA_API int dba_get_state(dba_ctx *ctx, float *score_host, uint64_t *met_mask_ho
                   int32_t *inprog_phrase_host, int32_t *inprog_pos_host, int32_t *length_host,
                   uint8_t *flags_host);
 
+/*
+ * Options, settable between dba_init and the first dba_step (DBA_ESTATE afterwards,
+ * DBA_EINVAL for an unknown option).
+ *   DBA_OPT_FUSED_LAUNCH  0 (default): a step is two launches - the kernel that streams the
+ *                         log-probs, then the per-sentence merge kernel; 1: one launch, in
+ *                         which the workgroup delivering a sentence's last row runs the merge.
+ *                         Same results; the two-launch form measured faster on MI355X.
+ */
+#define DBA_OPT_FUSED_LAUNCH 1
+DBA_API int dba_set_option(dba_ctx *ctx, int option, int value);
+
 /* Number of dba_step calls made so far (or DBA_EINVAL). */
 DBA_API int dba_steps_done(const dba_ctx *ctx);
 

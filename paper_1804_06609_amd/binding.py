@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdba.so")
 DBA_OK, DBA_EINVAL, DBA_ESTATE, DBA_EHIP, DBA_ENOMEM = 0, -1, -2, -3, -4
 DBA_FLAG_FINISHED, DBA_FLAG_DEAD = 1, 2
 DBA_MAX_BEAM, DBA_MAX_CONS_TOKENS = 64, 64
+DBA_OPT_FUSED_LAUNCH = 1
 
 _P = ctypes.c_void_p
 _I = ctypes.c_int
@@ -29,6 +30,7 @@ _SIGNATURES = {
     "dba_finalize": (_I, [_P] * 5),
     "dba_get_state": (_I, [_P] * 7),
     "dba_steps_done": (_I, [_P]),
+    "dba_set_option": (_I, [_P, _I, _I]),
     "dba_destroy": (None, [_P]),
     "dba_last_error": (ctypes.c_char_p, [_P]),
     "dba_debug_allocate": (_I, [_I] + [_P] * 5 + [ctypes.c_size_t, _P]),
@@ -113,6 +115,10 @@ def dba_get_state(ctx, score=None, met_mask=None, inprog_phrase=None, inprog_pos
     return _check(load().dba_get_state(ctx, _host(score, np.float32), _host(met_mask, np.uint64),
                                        _host(inprog_phrase, np.int32), _host(inprog_pos, np.int32),
                                        _host(length, np.int32), _host(flags, np.uint8)), ctx)
+
+
+def dba_set_option(ctx, option: int, value: int) -> int:
+    return _check(load().dba_set_option(ctx, option, value), ctx)
 
 
 def dba_steps_done(ctx) -> int:

@@ -330,9 +330,7 @@ struct dba_ctx {
     int tok_bits;
     int max_phrases;
     int steps;
-    int fused;
-    int unroll;
-    int waves;
+    int fused;                          // DBA_OPT_FUSED_LAUNCH
     size_t dyn_smem;
     unsigned char *ws;
     Layout L;
@@ -362,12 +360,6 @@ template <typename T>
 T *at(dba_ctx *c, size_t off)
 {
     return reinterpret_cast<T *>(c->ws + off);
-}
-
-int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return (v && *v) ? atoi(v) : dflt;
 }
 
 }  // namespace
@@ -470,10 +462,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->ws = static_cast<unsigned char *>(workspace_dev);
     c->L = L;
     c->stream = static_cast<hipStream_t>(hip_stream);
-    c->fused = env_int("DBA_FUSED", 0) ? 1 : 0;
-    c->unroll = env_int("DBA_UNROLL", 4);
-    c->waves = env_int("DBA_WAVES", 4);
-    if (c->waves != 1 && c->waves != 2 && c->waves != 4) c->waves = 4;
+    c->fused = 0;
     int npad = kWave;
     while (npad < k * (max_phrases + 2)) npad <<= 1;
     c->dyn_smem = (size_t)npad * sizeof(u64);
@@ -558,21 +547,14 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.hist_token = at<int32_t>(c, L.hist_token) + hrow;
     p.hist_backptr = at<int32_t>(c, L.hist_backptr) + hrow;
 
-    const dim3 grid((unsigned)(c->B * c->k));
+    // 4 wavefronts per row, 4 float4 per lane and tile: 1280 rows x 4 waves fill the 1024 SIMDs five
+    // deep with two 4 KB tiles in flight per wave (measured best on MI355X at V = 32000)
+    const dim3 grid((unsigned)(c->B * c->k)), block(kBlock);
     if (c->fused) {
-        switch (c->unroll) {
-            case 2: dba_step_fused_kernel<2><<<grid, dim3(kBlock), c->dyn_smem, c->stream>>>(p); break;
-            case 8: dba_step_fused_kernel<8><<<grid, dim3(kBlock), c->dyn_smem, c->stream>>>(p); break;
-            default: dba_step_fused_kernel<4><<<grid, dim3(kBlock), c->dyn_smem, c->stream>>>(p); break;
-        }
+        dba_step_fused_kernel<kTileLoads><<<grid, block, c->dyn_smem, c->stream>>>(p);
     } else {
-        const dim3 block((unsigned)(c->waves * kWave));
-        switch (c->unroll) {
-            case 2: dba_stream_kernel<2><<<grid, block, 0, c->stream>>>(p); break;
-            case 8: dba_stream_kernel<8><<<grid, block, 0, c->stream>>>(p); break;
-            default: dba_stream_kernel<4><<<grid, block, 0, c->stream>>>(p); break;
-        }
-        dba_merge_kernel<<<dim3((unsigned)c->B), dim3(kBlock), c->dyn_smem, c->stream>>>(p);
+        dba_stream_kernel<kTileLoads><<<grid, block, 0, c->stream>>>(p);
+        dba_merge_kernel<<<dim3((unsigned)c->B), block, c->dyn_smem, c->stream>>>(p);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_step: launch failed: %s", hipGetErrorString(e));
@@ -640,6 +622,16 @@ DBA_API int dba_get_state(dba_ctx *c, float *score_host, uint64_t *met_mask_host
 }
 
 DBA_API int dba_steps_done(const dba_ctx *c) { return c ? c->steps : DBA_EINVAL; }
+
+DBA_API int dba_set_option(dba_ctx *c, int option, int value)
+{
+    if (!c) return DBA_EINVAL;
+    if (c->steps != 0) return fail(c, DBA_ESTATE, "dba_set_option: options are fixed once the first step is taken");
+    switch (option) {
+        case DBA_OPT_FUSED_LAUNCH: c->fused = value ? 1 : 0; return DBA_OK;
+        default: return fail(c, DBA_EINVAL, "dba_set_option: unknown option %d", option);
+    }
+}
 
 DBA_API void dba_destroy(dba_ctx *c) { delete c; }
 

@@ -24,6 +24,7 @@ constexpr int kMaxBeam = 64;
 constexpr int kMaxCons = 64;          // constraint tokens (and phrases) per sentence
 constexpr int kBlock = 256;           // threads per workgroup
 constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kTileLoads = 4;         // float4 loads per lane and tile in the stream phase
 constexpr int kFinFinished = 1;       // beam-state flag: the hypothesis has generated end-of-sentence
 constexpr int kFinEosBlocked = 4;     // beam-state flag: constraints unmet, end-of-sentence not allowed (Sec. 3.3)
 
@@ -75,22 +76,25 @@ struct ConsTab {
     int poff[kMaxCons + 1];
 };
 
+// one hypothesis of the beam before the step, as the merge phase keeps it in LDS (two 16-byte reads)
+struct __attribute__((aligned(16))) HypState {
+    u64 met;       // bit i = constraint token i met
+    u64 inc;       // bit j = phrase j not complete
+    int ipq;       // phrase under way * 256 + tokens met in it, or -1
+    int nxt;       // next token of the phrase under way (-1: none under way)
+    int len;
+    int misc;      // finished flag | constraints met << 8
+};
+
 struct MergeSmem {
     u64 wl[kWavesPerBlock][kWave];
+    HypState hyp[kMaxBeam];
     u64 rb[kMaxBeam];                 // every row's best, as a selection-key body
     u64 sel[kMaxBeam];
-    u64 met[kMaxBeam];                // beam before the step ...
-    u64 inc[kMaxBeam];                // ... bit j = phrase j is not complete
-    float prev[kMaxBeam];
-    int ipq[kMaxBeam];
-    int nmet[kMaxBeam];
-    int nxt[kMaxBeam];                // next token of the phrase under way (-1: none under way)
-    int len[kMaxBeam];
     ConsTab ct;
     int cnt[kMaxCons + 1];
     int alloc[kMaxCons + 1];
     int start[kMaxCons + 1];
-    unsigned char fin[kMaxBeam];
     int ncand;
     int nsel;
 };
@@ -555,7 +559,6 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const int ftok = p.first_tok[(size_t)b * kMaxCons + lane];   // first token of this lane's phrase, -1 beyond P
     const int P = p.nphr[b];
     const u64 bloom = p.first_bloom[b];
-    const float ld_prev = p.score_cur[rs];
     const u64 ld_met = p.met_cur[rs];
     const u64 ld_inc = p.inc_cur[rs];
     const int ld_ipq = p.ipq_cur[rs];
@@ -590,14 +593,14 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         sm.nsel = 0;
     }
     if (tid < k) {
-        sm.prev[tid] = ld_prev;
-        sm.met[tid] = ld_met;
-        sm.inc[tid] = ld_inc;
-        sm.ipq[tid] = ld_ipq;
-        sm.nxt[tid] = ld_nxt;
-        sm.len[tid] = ld_len;
-        sm.nmet[tid] = __popcll(ld_met);
-        sm.fin[tid] = (unsigned char)(ld_fin & kFinFinished);
+        HypState hs;
+        hs.met = ld_met;
+        hs.inc = ld_inc;
+        hs.ipq = ld_ipq;
+        hs.nxt = ld_nxt;
+        hs.len = ld_len;
+        hs.misc = (ld_fin & kFinFinished) | (__popcll(ld_met) << 8);
+        sm.hyp[tid] = hs;
     }
 
     // ---- source 1: the sentence's k best (Sec. 3.1 item 1) = top k of the union of the
@@ -643,23 +646,28 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             h = (int)(code >> p.tok_bits);
             w = (int)(code & tokmask);
         }
+        const HypState hs = sm.hyp[h];
         const u64 match = first_token_matches(w, ftok, P, bloom);
         if (g_valid) {
-            g_bank = sm.nmet[h];
-            if (!sm.fin[h]) {
-                const int ipq = sm.ipq[h];
-                g_bank = nmet_after(g_bank, ipq < 0 ? -1 : (ipq >> 8), ipq < 0 ? 0 : (ipq & 255),
-                                    w == sm.nxt[h], match, sm.inc[h]);
-            }
+            g_bank = hs.misc >> 8;
+            if (!(hs.misc & kFinFinished))
+                g_bank = nmet_after(g_bank, hs.ipq < 0 ? -1 : (hs.ipq >> 8), hs.ipq < 0 ? 0 : (hs.ipq & 255),
+                                    w == hs.nxt, match, hs.inc);
         }
     }
     int total = __popcll(__ballot(g_valid));
+    u64 rbv[kRowsPerWave];
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        const int h = wave + i * kWavesPerBlock;
+        rbv[i] = h < k ? sm.rb[h] : 0ull;
+    }
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) {
         const int h = wave + i * kWavesPerBlock;
         if (h < k) {
             const u64 body = ck[i] & body_mask;
-            const bool valid = ck[i] != 0 && tau != 0 && body < tau && body != sm.rb[h];
+            const bool valid = ck[i] != 0 && tau != 0 && body < tau && body != rbv[i];
             if (!valid) ck[i] = 0;
             total += __popcll(__ballot(valid));
         }
@@ -767,15 +775,16 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         }
         const u64 match = first_token_matches(live ? token : -1, ftok, P, bloom);
         if (live) {
-            met2 = sm.met[parent];
-            inc2 = sm.inc[parent];
-            const int ipq = sm.ipq[parent];
+            const HypState hs = sm.hyp[parent];
+            met2 = hs.met;
+            inc2 = hs.inc;
+            const int ipq = hs.ipq;
             int ip = ipq < 0 ? -1 : (ipq >> 8), iq = ipq < 0 ? 0 : (ipq & 255);
-            const bool pfin = sm.fin[parent] != 0;
+            const bool pfin = (hs.misc & kFinFinished) != 0;
             if (!pfin) {
                 // add(token), Sec. 3.1: advance the phrase under way, or unwind it and let the
                 // token begin the lowest-index incomplete phrase that starts with it
-                if (ip >= 0 && token == sm.nxt[parent]) {
+                if (ip >= 0 && token == hs.nxt) {
                     const int o = sm.ct.poff[ip];
                     met2 |= 1ull << (o + iq);
                     ++iq;
@@ -790,7 +799,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
                         ip = -1;
                         iq = 0;
                     }
-                    const u64 startable = match & sm.inc[parent];
+                    const u64 startable = match & hs.inc;
                     if (startable) {
                         const int j = __ffsll((long long)startable) - 1;
                         const int o = sm.ct.poff[j];
@@ -807,7 +816,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             ipq2 = ip < 0 ? -1 : ((ip << 8) | iq);
             nxt2 = ip < 0 ? -1 : sm.ct.tok[sm.ct.poff[ip] + iq];
             fin2 = (pfin || token == p.eos_id) ? 1 : 0;
-            length = pfin ? sm.len[parent] : sm.len[parent] + 1;
+            length = pfin ? hs.len : hs.len + 1;
             flags = fin2;
         }
         if (lane < k) {

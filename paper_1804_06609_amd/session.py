@@ -17,7 +17,7 @@ class Session:
 
     def __init__(self, B: int, k: int, V: int, N: int, eos_id: int, pad_id: int,
                  cons_tokens: np.ndarray, phrase_offsets: np.ndarray, sent_offsets: np.ndarray,
-                 stream: Optional[torch.cuda.Stream] = None):
+                 stream: Optional[torch.cuda.Stream] = None, options: Optional[dict] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("libdba needs a GPU: no HIP device is visible")
         _b.load()
@@ -34,6 +34,8 @@ class Session:
         self.out_flags = torch.empty((B, k), dtype=torch.uint8, device="cuda")
         self.ctx = _b.dba_init(B, k, V, N, eos_id, pad_id, cons_tokens, phrase_offsets, sent_offsets,
                                base, nbytes, self.stream.cuda_stream)
+        for opt, val in (options or {}).items():
+            _b.dba_set_option(self.ctx, opt, val)
 
     def step(self, logp: torch.Tensor) -> None:
         """Enqueue one step; logp is a device fp32 tensor [B,k,V], contiguous."""

@@ -29,14 +29,15 @@ def _first_diff(name, got, want, t, sent_ids):
 
 
 def run_parity(wl: si.Workload, T: Optional[int] = None, oracle_sentences: Optional[Sequence[int]] = None,
-               check_state_every: int = 1, check_invariants: bool = True, progress: str = ""):
+               check_state_every: int = 1, check_invariants: bool = True, progress: str = "",
+               options: Optional[dict] = None):
     """Runs T steps of wl on the GPU and on the oracle (all sentences, or the sampled ones) and
     compares every step.  Returns the session's finalize() result after checking it too."""
     T = wl.T if T is None else T
     B, k, V = wl.B, wl.k, wl.V
     sent = list(range(B)) if oracle_sentences is None else sorted(oracle_sentences)
     toks, poff, soff = wl.csr()
-    ses = Session(B, k, V, T, wl.eos_id, wl.pad_id, toks, poff, soff)
+    ses = Session(B, k, V, T, wl.eos_id, wl.pad_id, toks, poff, soff, options=options)
     ob = oracle.BatchBeam(k, V, wl.constraints, wl.eos_id, wl.pad_id, sentences=sent)
     host = torch.empty((B, k, V), dtype=torch.float32, pin_memory=True)
     dev = torch.empty((B, k, V), dtype=torch.float32, device="cuda")

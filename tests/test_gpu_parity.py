@@ -129,6 +129,44 @@ def test_batch_equals_single_sentences(torch_gpu):
     assert fin[0].shape == (4, 12)
 
 
+@pytest.mark.parametrize("seed", [3, 6, 15])
+def test_one_launch_form_small(torch_gpu, seed):
+    """DBA_OPT_FUSED_LAUNCH: the one-launch form of the step gives the same results."""
+    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
+    k = [2, 13, 64][seed % 3]
+    wl = si.make_small(9100 + seed, 4, k, 1023, 10, max_phrases=5, max_len=4, dup_prob=0.35)
+    wl.eos_switch = 5
+    _harness().run_parity(wl, options={DBA_OPT_FUSED_LAUNCH: 1})
+
+
+def test_one_launch_form_config2(torch_gpu):
+    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
+    _harness().run_parity(si.make_config(2, T=15), options={DBA_OPT_FUSED_LAUNCH: 1})
+
+
+def test_call_order_errors(torch_gpu):
+    """More than N steps, and an option change after the first step, are refused (no launch)."""
+    import paper_1804_06609_amd as dba
+    from paper_1804_06609_amd.session import Session
+    wl = si.make_small(77, 2, 4, 64, 3)
+    toks, poff, soff = wl.csr()
+    ses = Session(wl.B, wl.k, wl.V, 3, wl.eos_id, wl.pad_id, toks, poff, soff)
+    dev = torch_gpu.from_numpy(wl.logp(0)).cuda()
+    with pytest.raises(dba.DbaError, match="unknown option"):
+        dba.dba_set_option(ses.ctx, 9999, 1)
+    ses.step(dev)
+    with pytest.raises(dba.DbaError, match="first step"):
+        dba.dba_set_option(ses.ctx, dba.DBA_OPT_FUSED_LAUNCH, 1)
+    mid = ses.finalize()                 # allowed after any number of steps
+    assert mid[0].shape == (wl.B, 3)
+    ses.step(dev)
+    ses.step(dev)
+    with pytest.raises(dba.DbaError):
+        ses.step(dev)
+    assert dba.dba_steps_done(ses.ctx) == 3
+    ses.close()
+
+
 def test_config1(torch_gpu):
     _harness().run_parity(si.make_config(1), progress="config1")
 
