@@ -47,9 +47,12 @@ def _load():
         lib.dba_oracle_add.argtypes = [ctypes.c_int, _P, _P, ctypes.c_uint64, ctypes.c_int,
                                        ctypes.c_int, ctypes.c_int, _P, _P, _P, _P, _P]
         lib.dba_oracle_step.restype = ctypes.c_int
-        lib.dba_oracle_step.argtypes = [ctypes.c_int] * 5 + [_P] * 22
+        lib.dba_oracle_allocate_fixed.restype = None
+        lib.dba_oracle_allocate_fixed.argtypes = [ctypes.c_int, ctypes.c_int, _P, _P]
+        lib.dba_oracle_step.argtypes = [ctypes.c_int] * 5 + [_P] * 22 + [ctypes.c_int, ctypes.c_int,
+                                                                        ctypes.c_float, _P]
         lib.dba_oracle_finalize.restype = ctypes.c_int
-        lib.dba_oracle_finalize.argtypes = [ctypes.c_int] * 4 + [_P] * 10
+        lib.dba_oracle_finalize.argtypes = [ctypes.c_int] * 4 + [_P] * 10 + [ctypes.c_int]
         _lib = lib
     return _lib
 
@@ -58,11 +61,12 @@ def _ptr(a: Optional[np.ndarray]):
     return None if a is None else a.ctypes.data
 
 
-def allocate(k: int, cnt: Sequence[int]) -> np.ndarray:
-    """Slots per bank for bank counts cnt[0..C] (Sec. 3.2)."""
+def allocate(k: int, cnt: Sequence[int], adjust: bool = True) -> np.ndarray:
+    """Slots per bank for bank counts cnt[0..C] (Sec. 3.2); adjust=False: Sec. 5's fixed split."""
     c = np.ascontiguousarray(cnt, dtype=np.int32)
     out = np.zeros_like(c)
-    _load().dba_oracle_allocate(int(k), len(c) - 1, c.ctypes.data, out.ctypes.data)
+    fn = _load().dba_oracle_allocate if adjust else _load().dba_oracle_allocate_fixed
+    fn(int(k), len(c) - 1, c.ctypes.data, out.ctypes.data)
     return out
 
 
@@ -92,8 +96,12 @@ def add(phrases, met: int, ip: int, iq: int, w: int):
 class SentenceBeam:
     """Beam of one sentence, advanced by dba_oracle_step."""
 
-    def __init__(self, k: int, V: int, phrases, eos_id: int, pad_id: int):
+    def __init__(self, k: int, V: int, phrases, eos_id: int, pad_id: int, adjust: bool = True,
+                 normalize_finished: bool = False, prune_threshold: Optional[float] = None):
         self.k, self.V, self.eos_id, self.pad_id = k, V, eos_id, pad_id
+        self.adjust, self.normalize_finished = bool(adjust), bool(normalize_finished)
+        self.prune_threshold = -1.0 if prune_threshold is None else float(prune_threshold)
+        self.all_finished = 0
         self.phrases = [list(p) for p in phrases]
         self.off, self.tok = _phrase_arrays(self.phrases)
         self.P = len(self.phrases)
@@ -130,6 +138,7 @@ class SentenceBeam:
         o_ip = np.empty(k, np.int32)
         o_iq = np.empty(k, np.int32)
         o_len = np.empty(k, np.int32)
+        done = np.zeros(1, np.int32)
         d_n = d_flat = d_bank = d_cnt = d_alloc = None
         if debug:
             cap = max(1, k * (self.P + 2))
@@ -143,7 +152,9 @@ class SentenceBeam:
             _ptr(self.score), _ptr(self.met), _ptr(self.ip), _ptr(self.iq), _ptr(fin),
             _ptr(self.len), _ptr(logp), _ptr(o_tok), _ptr(o_bp), _ptr(o_sc), _ptr(o_fl),
             _ptr(o_met), _ptr(o_ip), _ptr(o_iq), _ptr(o_len), _ptr(d_n), _ptr(d_flat),
-            _ptr(d_bank), _ptr(d_cnt), _ptr(d_alloc))
+            _ptr(d_bank), _ptr(d_cnt), _ptr(d_alloc), int(self.adjust), int(self.normalize_finished),
+            self.prune_threshold, _ptr(done))
+        self.all_finished = int(done[0])
         if rc != 0:
             raise ValueError("dba_oracle_step rejected its arguments")
         self.token, self.backptr, self.score, self.flags = o_tok, o_bp, o_sc, o_fl
@@ -166,7 +177,7 @@ class SentenceBeam:
         nm = self.nmet
         _load().dba_oracle_finalize(self.k, T, N, self.pad_id, _ptr(ht), _ptr(hb), _ptr(self.score),
                                     _ptr(self.flags), _ptr(self.len), _ptr(nm), _ptr(toks),
-                                    _ptr(ln), _ptr(sc), _ptr(stt))
+                                    _ptr(ln), _ptr(sc), _ptr(stt), int(self.normalize_finished))
         return toks, int(ln[0]), np.float32(sc[0]), int(stt[0])
 
 
@@ -174,9 +185,9 @@ class BatchBeam:
     """B independent sentence beams; step() may spread sentences over threads."""
 
     def __init__(self, k: int, V: int, constraints, eos_id: int, pad_id: int,
-                 sentences: Optional[Sequence[int]] = None):
+                 sentences: Optional[Sequence[int]] = None, **variants):
         self.sent_ids = list(range(len(constraints))) if sentences is None else list(sentences)
-        self.beams = [SentenceBeam(k, V, constraints[b], eos_id, pad_id) for b in self.sent_ids]
+        self.beams = [SentenceBeam(k, V, constraints[b], eos_id, pad_id, **variants) for b in self.sent_ids]
         self.k, self.V = k, V
 
     def step(self, logp: np.ndarray, threads: int = 1, debug: bool = False):

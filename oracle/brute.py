@@ -94,11 +94,15 @@ def allocate(k: int, cnt: List[int]) -> List[int]:
     return alloc
 
 
-def step(beam: List[Optional[Hyp]], logp: np.ndarray, phrases, eos_id: int, pad_id: int
+def step(beam: List[Optional[Hyp]], logp: np.ndarray, phrases, eos_id: int, pad_id: int,
+         adjust: bool = True, normalize: bool = False, prune: Optional[float] = None
          ) -> Tuple[List[Optional[Tuple[int, int, Hyp]]], dict]:
     """One step.  beam[h] is None for an empty slot.  Returns the new beam as
     (token, parent, hypothesis) triples best first (None = empty slot) and a
-    dict of intermediate facts."""
+    dict of intermediate facts.  adjust=False: bank sizes stay at the base split
+    (Sec. 5); normalize: a hypothesis completing now is stored with sum/length
+    (Sec. 4); prune: hypotheses below best-completed minus this are struck out
+    (Sec. 4, Sec. 6.3)."""
     k, V = logp.shape
     C = sum(len(p) for p in phrases)
     s = np.full((k, V), -np.inf, dtype=np.float32)
@@ -141,12 +145,26 @@ def step(beam: List[Optional[Hyp]], logp: np.ndarray, phrases, eos_id: int, pad_
     cnt = [0] * (C + 1)
     for it in items:
         cnt[it[0]] += 1
-    alloc = allocate(k, cnt)
+    if adjust:
+        alloc = allocate(k, cnt)
+    else:
+        share, rest = divmod(k, C + 1)
+        alloc = [min(cnt[b], share + (rest if b == C else 0)) for b in range(C + 1)]
     chosen = []
     for b in range(C + 1):
         members = sorted((it for it in items if it[0] == b), key=lambda it: (-it[1], it[2]))
         chosen.extend(members[:alloc[b]])
     chosen.sort(key=lambda it: (-it[1], it[2]))
     out: List[Optional[Tuple[int, int, Hyp]]] = [(it[3], it[4], it[5]) for it in chosen]
+    if normalize:
+        for w, h, new in out:
+            if new.finished and not beam[h].finished:
+                new.score = np.float32(new.score) / np.float32(new.length)
+    if prune is not None:
+        done = [np.float32(new.score) for _, _, new in out if new.finished]
+        if done:
+            cut = np.float32(max(done)) - np.float32(prune)
+            out = [x for x in out if not np.float32(x[2].score) < cut]
+    stop = bool(out) and all(new.finished for _, _, new in out)
     out += [None] * (k - len(out))
-    return out, dict(cands=sorted(cands), topk=topk, cnt=cnt, alloc=alloc)
+    return out, dict(cands=sorted(cands), topk=topk, cnt=cnt, alloc=alloc, all_finished=stop)

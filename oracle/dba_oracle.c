@@ -33,6 +33,20 @@
  * adjustment, first-tokens of other phrases being expandable while one phrase
  * is in progress, the lowest-phrase-index rule and restart-after-unwind of
  * add().
+ *
+ * Variants of the experimental set-up (Sec. 4, Sec. 5, Sec. 6.3), each off by
+ * default and switched by an argument of dba_oracle_step: allocation without
+ * adjustment (the GBS simulation of Sec. 5), scores of completed hypotheses
+ * divided by their length while they sit on the beam (Sec. 4; Fig. 9 caption),
+ * threshold pruning against the best completed hypothesis (Sec. 4, Sec. 6.3)
+ * and the all-completed stopping test (Sec. 4).  Pinned by tests: the
+ * stored score of a completed hypothesis equals the fp32 sum of the log-probs
+ * along its back-pointer path divided by its length; a pruned step equals the
+ * unpruned step with the losers struck out; survivors lie within the
+ * threshold of the best completed one; brute-force enumeration.  Unpinned
+ * readings: raw sums decide the selection inside the step in which a
+ * hypothesis completes; the pruning cut-off is the fp32 difference best -
+ * threshold and a score equal to it survives.
  */
 #include <math.h>
 #include <stdint.h>
@@ -168,6 +182,18 @@ void dba_oracle_allocate(int k, int C, const int32_t *cnt, int32_t *alloc)
     }
 }
 
+/* Allocation with the adjustment switched off (Sec. 5, the simulated GBS
+ * baseline: the room of a bank does not change): the base split of Sec. 3.2;
+ * a bank with fewer candidates than slots leaves the rest of its slots empty. */
+void dba_oracle_allocate_fixed(int k, int C, const int32_t *cnt, int32_t *alloc)
+{
+    const int base = k / (C + 1);
+    for (int b = 0; b <= C; ++b) alloc[b] = base;
+    alloc[C] += k - base * (C + 1);
+    for (int b = 0; b <= C; ++b)
+        if (alloc[b] > cnt[b]) alloc[b] = cnt[b];
+}
+
 /* state transition alone, for direct tests of add() and the expandable set */
 void dba_oracle_add(int P, const int32_t *off, const int32_t *tok, uint64_t met_in,
                     int ip_in, int iq_in, int w, uint64_t *met_out, int *ip_out, int *iq_out,
@@ -229,6 +255,21 @@ static void sort_cands(cand_t **v, int n)
  *      length); unused slots: token pad, parent -1, score -inf, flag DEAD.
  * dbg_* (each may be NULL): candidate count, per-candidate flat/bank (room for
  *      k*(P+2)), bank counts and final allocation [C+1].
+ * Variants (the paper's defaults for its experiments differ from the bare
+ * algorithm; 1, 0, negative, NULL give the bare algorithm):
+ *   adjust              0: no adjustment of the bank sizes (Sec. 5).
+ *   normalize_finished  1: a hypothesis that generates end-of-sentence in this
+ *      step is stored with score = sum / length (one fp32 division, the length
+ *      counts end-of-sentence) and keeps that score while it stays on the beam
+ *      (Sec. 4; Fig. 9 caption: only finished hypotheses are normalised).
+ *      Reading: inside this step it still competes with its raw sum - the
+ *      entry of the scores matrix - and the new beam is ordered by those sums.
+ *   prune_threshold     >= 0: after the new beam is formed, every hypothesis,
+ *      completed or not, whose stored score is below (best stored score of a
+ *      completed hypothesis on the new beam) - threshold is removed (Sec. 4);
+ *      the rest close ranks in order.  No completed hypothesis: no pruning.
+ *   out_all_finished    receives 1 when the new beam is not empty and all its
+ *      hypotheses are completed - the stopping test of Sec. 4.
  * Returns 0, or -1 on bad arguments.
  */
 int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *phrase_off,
@@ -238,7 +279,8 @@ int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *
                     int32_t *out_backptr, float *out_score, uint8_t *out_flags,
                     uint64_t *out_met, int32_t *out_ip, int32_t *out_iq, int32_t *out_len,
                     int32_t *dbg_ncand, int64_t *dbg_flat, int32_t *dbg_bank, int32_t *dbg_cnt,
-                    int32_t *dbg_alloc)
+                    int32_t *dbg_alloc, int adjust, int normalize_finished, float prune_threshold,
+                    int32_t *out_all_finished)
 {
     if (k < 1 || V < 1 || P < 0) return -1;
     cons_t c = {P, phrase_off[P], phrase_off, tokens};
@@ -336,7 +378,10 @@ int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *
         cand[i].bank = count_met(&c, &cand[i].st);
         cnt[cand[i].bank] += 1;
     }
-    dba_oracle_allocate(k, C, cnt, alloc);
+    if (adjust)
+        dba_oracle_allocate(k, C, cnt, alloc);
+    else
+        dba_oracle_allocate_fixed(k, C, cnt, alloc);
 
     /* per bank: best first, take as many as the bank was given */
     cand_t **order = (cand_t **)malloc((size_t)(cap > 0 ? cap : 1) * sizeof(cand_t *));
@@ -371,6 +416,7 @@ int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *
             out_ip[i] = x->st.ip;
             out_iq[i] = x->st.iq;
             out_len[i] = pf ? len_in[x->h] : len_in[x->h] + 1;
+            if (normalize_finished && f && !pf) out_score[i] = out_score[i] / (float)out_len[i];
         } else {
             out_token[i] = pad_id;
             out_backptr[i] = -1;
@@ -381,6 +427,51 @@ int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *
             out_iq[i] = 0;
             out_len[i] = 0;
         }
+    }
+
+    /* threshold pruning (Sec. 4, Sec. 6.3) */
+    if (prune_threshold >= 0.0f) {
+        int have = 0;
+        float best = NEG_INF;
+        for (int i = 0; i < nsel; ++i)
+            if ((out_flags[i] & FLAG_FINISHED) && (!have || out_score[i] > best)) {
+                best = out_score[i];
+                have = 1;
+            }
+        if (have) {
+            const float cut = best - prune_threshold;
+            int m = 0;
+            for (int i = 0; i < nsel; ++i) {
+                if (!(out_score[i] >= cut)) continue;
+                out_token[m] = out_token[i];
+                out_backptr[m] = out_backptr[i];
+                out_score[m] = out_score[i];
+                out_flags[m] = out_flags[i];
+                out_met[m] = out_met[i];
+                out_ip[m] = out_ip[i];
+                out_iq[m] = out_iq[i];
+                out_len[m] = out_len[i];
+                ++m;
+            }
+            for (int i = m; i < nsel; ++i) {
+                out_token[i] = pad_id;
+                out_backptr[i] = -1;
+                out_score[i] = NEG_INF;
+                out_flags[i] = FLAG_DEAD;
+                out_met[i] = 0;
+                out_ip[i] = -1;
+                out_iq[i] = 0;
+                out_len[i] = 0;
+            }
+            nsel = m;
+        }
+    }
+    /* stopping test (Sec. 4) */
+    if (out_all_finished) {
+        int all = nsel > 0;
+        for (int i = 0; i < nsel; ++i)
+            if (!(out_flags[i] & FLAG_FINISHED)) all = 0;
+        *out_all_finished = all;
     }
 
     if (dbg_ncand) *dbg_ncand = n;
@@ -412,14 +503,19 @@ int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *
  * no completed hypothesis the status is 0 and the fallback is the live slot
  * with most constraints met, then best raw score, then lowest slot.
  *
+ * scores_normalized = 1: the beam already holds sum/length for completed
+ * hypotheses (normalize_finished of the step), so they are ranked by the
+ * stored score as it is.
+ *
  * hist_token / hist_backptr: [T][k] records of the T steps taken.
  * final beam: score, flags, len, nmet [k].
- * out_tokens [N] (pad-filled), out_len, out_score (raw cumulative), out_status.
+ * out_tokens [N] (pad-filled), out_len, out_score (as stored on the beam), out_status.
  */
 int dba_oracle_finalize(int k, int T, int N, int pad_id, const int32_t *hist_token,
                         const int32_t *hist_backptr, const float *score, const uint8_t *flags,
                         const int32_t *len, const int32_t *nmet, int32_t *out_tokens,
-                        int32_t *out_len, float *out_score, int32_t *out_status)
+                        int32_t *out_len, float *out_score, int32_t *out_status,
+                        int scores_normalized)
 {
     for (int i = 0; i < N; ++i) out_tokens[i] = pad_id;
     *out_len = 0;
@@ -430,7 +526,7 @@ int dba_oracle_finalize(int k, int T, int N, int pad_id, const int32_t *hist_tok
     float bestq = 0.0f;
     for (int h = 0; h < k; ++h) {
         if ((flags[h] & FLAG_DEAD) || !(flags[h] & FLAG_FINISHED)) continue;
-        const float q = score[h] / (float)len[h];
+        const float q = scores_normalized ? score[h] : score[h] / (float)len[h];
         if (best < 0 || q > bestq) {
             best = h;
             bestq = q;

@@ -1,0 +1,224 @@
+"""Pins for the oracle's variants of the experimental set-up: allocation without adjustment
+(Sec. 5, the simulated GBS baseline), completed hypotheses stored with score/length (Sec. 4;
+Fig. 9 caption), threshold pruning against the best completed hypothesis (Sec. 4, Sec. 6.3) and
+the all-completed stopping test (Sec. 4).  CPU only."""
+from __future__ import annotations
+
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+from oracle import brute
+
+
+# ---- Sec. 5: the room of a bank does not change -------------------------------------------
+def test_fixed_allocation_is_the_clipped_base_split():
+    for k in range(1, 9):
+        for C in range(0, 5):
+            base, rem = divmod(k, C + 1)
+            for cnt in itertools.product(range(0, 5), repeat=C + 1):
+                a = oracle.allocate(k, cnt, adjust=False)
+                for b in range(C + 1):
+                    room = base + (rem if b == C else 0)
+                    assert a[b] == min(room, cnt[b])
+                assert a.sum() <= k
+                # where every bank can fill its room, adjustment has nothing to move
+                if all(cnt[b] >= base + (rem if b == C else 0) for b in range(C + 1)):
+                    assert list(a) == list(oracle.allocate(k, cnt, adjust=True))
+                # adjustment only ever fills more of the beam
+                assert a.sum() <= oracle.allocate(k, cnt, adjust=True).sum()
+
+
+def test_gbs_simulation_gives_every_bank_the_base_beam():
+    """Sec. 5: beam b(C+1) and no adjustment = b slots for every bank, as in grid beam search."""
+    for b, C in itertools.product((1, 5, 10), (0, 1, 3, 7)):
+        k = b * (C + 1)
+        cnt = [1000] * (C + 1)
+        assert list(oracle.allocate(k, cnt, adjust=False)) == [b] * (C + 1)
+        cnt[C // 2] = 2
+        a = oracle.allocate(k, cnt, adjust=False)
+        assert a[C // 2] == min(2, b) and all(a[x] == b for x in range(C + 1) if x != C // 2)
+
+
+# ---- brute-force enumeration of the variants ------------------------------------------------
+VARIANTS = [
+    dict(adjust=False),
+    dict(normalize=True),
+    dict(prune=3.0),
+    dict(prune=0.0, normalize=True),
+    dict(adjust=False, normalize=True, prune=6.0),
+]
+
+
+def _oracle_kwargs(v):
+    return dict(adjust=v.get("adjust", True), normalize_finished=v.get("normalize", False),
+                prune_threshold=v.get("prune"))
+
+
+@pytest.mark.parametrize("vi", range(len(VARIANTS)))
+@pytest.mark.parametrize("seed", range(40))
+def test_variants_match_brute_force(seed, vi):
+    v = VARIANTS[vi]
+    rs = si.Stream(seed, 177)
+    k = rs.randint(2, 6)
+    V = rs.randint(6, 40)
+    T = rs.randint(5, 10)
+    wl = si.make_small(500 + seed, 1, k, V, T, max_phrases=3, max_len=3, dup_prob=0.4)
+    wl.eos_switch = 2
+    wl.eos_high = 0.5
+    phrases = wl.constraints[0]
+    bm = oracle.SentenceBeam(k, V, phrases, wl.eos_id, wl.pad_id, **_oracle_kwargs(v))
+    beam = [None] * k
+    beam[0] = brute.Hyp(np.float32(0.0), [0] * len(phrases))
+    for t in range(T):
+        logp = wl.logp(t)[0]
+        new, info = brute.step(beam, logp, phrases, wl.eos_id, wl.pad_id, **v)
+        bm.step(logp, debug=True)
+        assert list(bm.dbg["alloc"]) == info["alloc"]
+        assert bm.all_finished == int(info["all_finished"])
+        for i, item in enumerate(new):
+            if item is None:
+                assert bm.flags[i] == oracle.FLAG_DEAD and bm.backptr[i] == -1
+                assert bm.token[i] == wl.pad_id and bm.score[i] == -np.inf and bm.len[i] == 0
+                continue
+            w, h, hyp = item
+            assert (int(bm.token[i]), int(bm.backptr[i])) == (w, h)
+            assert np.float32(bm.score[i]).tobytes() == np.float32(hyp.score).tobytes()
+            assert int(bm.met[i]) == brute.met_mask(phrases, hyp)
+            assert bool(bm.flags[i] & oracle.FLAG_FINISHED) == hyp.finished
+            assert int(bm.len[i]) == hyp.length
+        beam = [None if it is None else it[2] for it in new]
+
+
+# ---- Sec. 4: score / number of words, for completed hypotheses only ---------------------------
+def _path_sum(logps, hist_tok, hist_bp, t, slot, eos_id):
+    """fp32 sum of the log-probs along the back-pointer path that ends in `slot` after step t,
+    added in the order of generation, up to and including end-of-sentence."""
+    path = []
+    for u in range(t, -1, -1):
+        parent = int(hist_bp[u][slot])
+        path.append((u, parent, int(hist_tok[u][slot])))
+        slot = parent
+    s = np.float32(0.0)
+    n = 0
+    for u, parent, w in reversed(path):
+        s = np.float32(s + logps[u][parent, w])
+        n += 1
+        if w == eos_id:
+            break
+    return s, n
+
+
+@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("normalize", [False, True])
+def test_stored_score_is_the_path_sum_over_the_length(seed, normalize):
+    k, V, T = 6, 50, 14
+    wl = si.make_small(900 + seed, 1, k, V, T, max_phrases=2, max_len=2)
+    wl.eos_switch = 3
+    wl.eos_high = 0.0
+    phrases = wl.constraints[0]
+    bm = oracle.SentenceBeam(k, V, phrases, wl.eos_id, wl.pad_id, normalize_finished=normalize)
+    logps, n_done = [], 0
+    for t in range(T):
+        logps.append(wl.logp(t)[0].copy())
+        bm.step(logps[-1])
+        for i in range(k):
+            if bm.flags[i] == oracle.FLAG_DEAD:
+                continue
+            s, n = _path_sum(logps, bm.hist_token, bm.hist_backptr, t, i, wl.eos_id)
+            assert n == bm.len[i]
+            if (bm.flags[i] & oracle.FLAG_FINISHED) and normalize:
+                assert bm.score[i] == np.float32(s) / np.float32(n)
+                n_done += 1
+            else:
+                assert bm.score[i] == s
+    if normalize:
+        assert n_done > 0
+        # the returned hypothesis is the completed one with the best stored score
+        toks, ln, sc, status = bm.finalize(T)
+        done = [i for i in range(k) if bm.flags[i] & oracle.FLAG_FINISHED]
+        assert status == 1 and sc == max(bm.score[i] for i in done)
+        first = min(i for i in done if bm.score[i] == sc)
+        assert ln == bm.len[first] and toks[ln - 1] == wl.eos_id
+
+
+# ---- Sec. 4 / Sec. 6.3: threshold pruning ---------------------------------------------------
+def _clone(bm, **kw):
+    c = oracle.SentenceBeam(bm.k, bm.V, bm.phrases, bm.eos_id, bm.pad_id, **kw)
+    for name in ("score", "met", "ip", "iq", "flags", "len", "token", "backptr"):
+        setattr(c, name, getattr(bm, name).copy())
+    return c
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_pruned_step_is_the_unpruned_step_with_the_losers_struck_out(seed):
+    k, V, T = 8, 60, 12
+    theta = [0.0, 1.5, 4.0, 20.0][seed % 4]
+    normalize = bool(seed & 4)
+    wl = si.make_small(1300 + seed, 1, k, V, T, max_phrases=2, max_len=2)
+    wl.eos_switch = 2
+    wl.eos_high = -1.0
+    bm = oracle.SentenceBeam(k, V, wl.constraints[0], wl.eos_id, wl.pad_id,
+                             normalize_finished=normalize, prune_threshold=theta)
+    n_pruned = 0
+    for t in range(T):
+        logp = wl.logp(t)[0]
+        plain = _clone(bm, normalize_finished=normalize).step(logp)
+        bm.step(logp)
+        live = plain.flags != oracle.FLAG_DEAD
+        done = live & ((plain.flags & oracle.FLAG_FINISHED) != 0)
+        keep = live.copy()
+        if done.any():
+            best = plain.score[done].max()
+            assert best in bm.score                                  # the best completed one stays
+            keep &= ~(plain.score < np.float32(best - np.float32(theta)))
+            # survivors are within the threshold of the best completed hypothesis
+            assert (best.astype(np.float64) - plain.score[keep].astype(np.float64) <= theta + 1e-4).all()
+        idx = np.flatnonzero(keep)
+        n_pruned += int(live.sum()) - len(idx)
+        for name in ("token", "backptr", "score", "flags", "met", "ip", "iq", "len"):
+            got, want = getattr(bm, name), getattr(plain, name)
+            assert got[:len(idx)].tobytes() == want[idx].tobytes(), (name, t)
+        assert (bm.flags[len(idx):] == oracle.FLAG_DEAD).all() and (bm.score[len(idx):] == -np.inf).all()
+        assert (bm.backptr[len(idx):] == -1).all() and (bm.token[len(idx):] == wl.pad_id).all()
+        assert bm.all_finished == int(len(idx) > 0 and ((bm.flags[:len(idx)] & 1) == 1).all())
+    if theta < 20.0:
+        assert n_pruned > 0
+
+
+def test_a_huge_threshold_prunes_nothing_and_a_finished_beam_stays_put():
+    k, V, T = 5, 40, 16
+    wl = si.make_small(77, 1, k, V, T, max_phrases=2, max_len=2)
+    wl.eos_switch = 2
+    wl.eos_high = 3.0
+    a = oracle.SentenceBeam(k, V, wl.constraints[0], wl.eos_id, wl.pad_id)
+    b = oracle.SentenceBeam(k, V, wl.constraints[0], wl.eos_id, wl.pad_id, prune_threshold=1e30)
+    c = oracle.SentenceBeam(k, V, wl.constraints[0], wl.eos_id, wl.pad_id, normalize_finished=True,
+                            prune_threshold=2.0)
+    stopped_at = None
+    for t in range(T):
+        logp = wl.logp(t)[0]
+        a.step(logp)
+        b.step(logp)
+        before = (c.score.copy(), c.len.copy(), c.met.copy())
+        was_done = c.all_finished
+        c.step(logp)
+        for name in ("token", "backptr", "score", "flags", "met", "len"):
+            assert getattr(a, name).tobytes() == getattr(b, name).tobytes()
+        if was_done:
+            # Sec. 4: decoding may stop here - further steps only carry the same hypotheses along
+            # (now in the order of their stored scores)
+            assert c.all_finished
+            live = c.flags != oracle.FLAG_DEAD
+            par = c.backptr[live]
+            assert sorted(par.tolist()) == list(range(int(live.sum()))) and (c.token[live] == wl.pad_id).all()
+            assert c.score[live].tobytes() == before[0][par].tobytes()
+            assert c.len[live].tobytes() == before[1][par].tobytes()
+            assert c.met[live].tobytes() == before[2][par].tobytes()
+            assert (c.score[live][:-1] >= c.score[live][1:]).all()
+        elif c.all_finished:
+            stopped_at = t
+    assert stopped_at is not None and stopped_at < T - 1
