@@ -118,7 +118,8 @@ DBA_API int dba_step(dba_ctx *ctx, const float *logp_dev, int32_t *out_token_dev
  *
  *   out_tokens_host host [B,N] int32, pad_id-filled beyond the length
  *   out_len_host    host [B]   int32, tokens incl. end-of-sentence
- *   out_score_host  host [B]   fp32, raw cumulative score of the returned hypothesis
+ *   out_score_host  host [B]   fp32, score of the returned hypothesis as the beam holds it
+ *                   (cumulative; per word under DBA_OPT_NORMALIZE_FINISHED)
  *   out_status_host host [B]   int32, 1 = a completed hypothesis was found; 0 = none (the
  *                   returned one is then the live slot with most constraints met,
  *                   then best score)
@@ -140,14 +141,42 @@ DBA_API int dba_get_state(dba_ctx *ctx, float *score_host, uint64_t *met_mask_ho
 
 /*
  * Options, settable between dba_init and the first dba_step (DBA_ESTATE afterwards,
- * DBA_EINVAL for an unknown option).
- *   DBA_OPT_FUSED_LAUNCH  0 (default): a step is two launches - the kernel that streams the
- *                         log-probs, then the per-sentence merge kernel; 1: one launch, in
- *                         which the workgroup delivering a sentence's last row runs the merge.
- *                         Same results; the two-launch form measured faster on MI355X.
+ * DBA_EINVAL for an unknown option or a NaN value).  The defaults give the bare
+ * algorithm of Alg. 2; the others are the settings of the paper's experiments.
+ *   DBA_OPT_FUSED_LAUNCH        0 (default): a step is two launches - the kernel that streams
+ *                               the log-probs, then the per-sentence merge kernel; non-zero: one
+ *                               launch, in which the workgroup delivering a sentence's last row
+ *                               runs the merge.  Same results; two launches measured faster.
+ *   DBA_OPT_ADJUSTMENT          1 (default): bank sizes are adjusted as in Sec. 3.2; 0: they stay
+ *                               at the base split and a bank that cannot fill its slots leaves
+ *                               them empty - with k = b(C+1) the grid-beam-search simulation of
+ *                               Sec. 5.
+ *   DBA_OPT_NORMALIZE_FINISHED  0 (default): the beam holds cumulative scores and dba_finalize
+ *                               divides by the length; non-zero: a hypothesis that generates
+ *                               end-of-sentence is stored with score / length (one fp32 division,
+ *                               the length counts end-of-sentence) from that step on, as in
+ *                               Sec. 4 and the caption of Fig. 9; inside the step in which it
+ *                               completes it still competes with its cumulative score, and
+ *                               dba_finalize ranks completed hypotheses by the stored score.
+ *   DBA_OPT_PRUNE_THRESHOLD     negative (default): no pruning; t >= 0: after every step, each
+ *                               hypothesis, completed or not, whose stored score is below
+ *                               (best stored score of a completed hypothesis on the new beam) - t
+ *                               is removed and the others close ranks (Sec. 4, Sec. 6.3; the
+ *                               paper uses 20).  The value is rounded to fp32; the difference is
+ *                               one fp32 subtraction and a score equal to it survives.
  */
 #define DBA_OPT_FUSED_LAUNCH 1
-DBA_API int dba_set_option(dba_ctx *ctx, int option, int value);
+#define DBA_OPT_ADJUSTMENT 2
+#define DBA_OPT_NORMALIZE_FINISHED 3
+#define DBA_OPT_PRUNE_THRESHOLD 4
+DBA_API int dba_set_option(dba_ctx *ctx, int option, double value);
+
+/*
+ * The stopping test of Sec. 4 (synchronises the stream): all_finished_host, host [B] uint8,
+ * receives 1 for every sentence whose beam is not empty and holds completed hypotheses only
+ * (further steps would only carry them along), else 0.
+ */
+DBA_API int dba_get_finished(dba_ctx *ctx, uint8_t *all_finished_host);
 
 /* Number of dba_step calls made so far (or DBA_EINVAL). */
 DBA_API int dba_steps_done(const dba_ctx *ctx);
@@ -161,13 +190,13 @@ DBA_API const char *dba_last_error(const dba_ctx *ctx);
 
 /*
  * Diagnostic: runs the device-side bank allocation of Sec. 3.2 alone, on one
- * wavefront, for n_cases independent problems.
+ * wavefront, for n_cases independent problems (adjust = 0: without the adjustment, Sec. 5).
  *   k_host [n_cases], C_host [n_cases] (0..64), cnt_host [n_cases][65] candidates per bank,
  *   alloc_host [n_cases][65] receives the slots per bank.  All host pointers; the call
  * stages them through `scratch_dev` (device, >= n_cases*132*4 bytes) on `hip_stream`
  * and synchronises.
  */
-DBA_API int dba_debug_allocate(int n_cases, const int32_t *k_host, const int32_t *C_host,
+DBA_API int dba_debug_allocate(int n_cases, int adjust, const int32_t *k_host, const int32_t *C_host,
                        const int32_t *cnt_host, int32_t *alloc_host, void *scratch_dev,
                        size_t scratch_bytes, void *hip_stream);
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdba.so")
 DBA_OK, DBA_EINVAL, DBA_ESTATE, DBA_EHIP, DBA_ENOMEM = 0, -1, -2, -3, -4
 DBA_FLAG_FINISHED, DBA_FLAG_DEAD = 1, 2
 DBA_MAX_BEAM, DBA_MAX_CONS_TOKENS = 64, 64
-DBA_OPT_FUSED_LAUNCH = 1
+DBA_OPT_FUSED_LAUNCH, DBA_OPT_ADJUSTMENT, DBA_OPT_NORMALIZE_FINISHED, DBA_OPT_PRUNE_THRESHOLD = 1, 2, 3, 4
 
 _P = ctypes.c_void_p
 _I = ctypes.c_int
@@ -30,10 +30,11 @@ _SIGNATURES = {
     "dba_finalize": (_I, [_P] * 5),
     "dba_get_state": (_I, [_P] * 7),
     "dba_steps_done": (_I, [_P]),
-    "dba_set_option": (_I, [_P, _I, _I]),
+    "dba_set_option": (_I, [_P, _I, ctypes.c_double]),
+    "dba_get_finished": (_I, [_P, _P]),
     "dba_destroy": (None, [_P]),
     "dba_last_error": (ctypes.c_char_p, [_P]),
-    "dba_debug_allocate": (_I, [_I] + [_P] * 5 + [ctypes.c_size_t, _P]),
+    "dba_debug_allocate": (_I, [_I, _I] + [_P] * 5 + [ctypes.c_size_t, _P]),
     "dba_debug_wave_select": (_I, [_I] + [_P] * 5 + [ctypes.c_size_t, _P]),
 }
 
@@ -117,8 +118,12 @@ def dba_get_state(ctx, score=None, met_mask=None, inprog_phrase=None, inprog_pos
                                        _host(length, np.int32), _host(flags, np.uint8)), ctx)
 
 
-def dba_set_option(ctx, option: int, value: int) -> int:
-    return _check(load().dba_set_option(ctx, option, value), ctx)
+def dba_set_option(ctx, option: int, value: float) -> int:
+    return _check(load().dba_set_option(ctx, option, float(value)), ctx)
+
+
+def dba_get_finished(ctx, all_finished: np.ndarray) -> int:
+    return _check(load().dba_get_finished(ctx, _host(all_finished, np.uint8)), ctx)
 
 
 def dba_steps_done(ctx) -> int:
@@ -130,10 +135,10 @@ def dba_destroy(ctx) -> None:
 
 
 def dba_debug_allocate(k: np.ndarray, C: np.ndarray, cnt: np.ndarray, alloc: np.ndarray,
-                       scratch_dev: int, scratch_bytes: int, hip_stream: int = 0) -> int:
+                       scratch_dev: int, scratch_bytes: int, hip_stream: int = 0, adjust: bool = True) -> int:
     n = int(k.shape[0])
     assert cnt.shape == (n, 65) and alloc.shape == (n, 65)
-    return _check(load().dba_debug_allocate(n, _host(k, np.int32), _host(C, np.int32),
+    return _check(load().dba_debug_allocate(n, int(bool(adjust)), _host(k, np.int32), _host(C, np.int32),
                                             _host(cnt, np.int32), _host(alloc, np.int32),
                                             scratch_dev, scratch_bytes, hip_stream or None))
 

@@ -176,7 +176,7 @@ __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float
 // decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0
 __global__ void dba_init_state_kernel(int B, int k, const int32_t *phr_off, const int32_t *nphr, float *score,
                                       u64 *met, int32_t *ipq, int32_t *len, uint8_t *fin, u64 *inc,
-                                      int32_t *nxt, unsigned int *counters)
+                                      int32_t *nxt, unsigned int *counters, uint8_t *all_finished)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < B * k) {
@@ -191,11 +191,14 @@ __global__ void dba_init_state_kernel(int B, int k, const int32_t *phr_off, cons
         inc[i] = (h == 0 && P > 0) ? (P == 64 ? ~0ull : ((1ull << P) - 1ull)) : 0ull;
         nxt[i] = -1;
     }
-    if (i < B) counters[i] = 0;
+    if (i < B) {
+        counters[i] = 0;
+        all_finished[i] = 0;
+    }
 }
 
 // End of decoding (Sec. 3.3, length normalisation of Sec. 4): one thread per sentence.
-__global__ void dba_finalize_kernel(int B, int k, int T, int N, int pad_id,
+__global__ void dba_finalize_kernel(int B, int k, int T, int N, int pad_id, int normalized,
                                     const int32_t *hist_token, const int32_t *hist_backptr,
                                     const float *score, const u64 *met, const int32_t *len,
                                     const uint8_t *fin, int32_t *out_tokens, int32_t *out_len,
@@ -214,7 +217,8 @@ __global__ void dba_finalize_kernel(int B, int k, int T, int N, int pad_id,
     float bestq = 0.0f;
     for (int h = 0; h < k; ++h) {
         if (!(score[o + h] > -INFINITY) || !(fin[o + h] & kFinFinished)) continue;
-        const float q = __fdiv_rn(score[o + h], (float)len[o + h]);
+        // per-word score; already held by the beam when completed hypotheses are stored that way
+        const float q = normalized ? score[o + h] : __fdiv_rn(score[o + h], (float)len[o + h]);
         if (best < 0 || q > bestq) {
             best = h;
             bestq = q;
@@ -246,7 +250,7 @@ __global__ void dba_finalize_kernel(int B, int k, int T, int N, int pad_id,
 }
 
 // Diagnostic: the allocation of Sec. 3.2 alone, one wavefront per case.
-__global__ void dba_allocate_kernel(int n_cases, const int32_t *kk, const int32_t *CC,
+__global__ void dba_allocate_kernel(int n_cases, int adjust, const int32_t *kk, const int32_t *CC,
                                     const int32_t *cnt, int32_t *alloc)
 {
     const int i = blockIdx.x;
@@ -256,7 +260,7 @@ __global__ void dba_allocate_kernel(int n_cases, const int32_t *kk, const int32_
     const int c = cnt[(size_t)i * 65 + lane];
     const int c64 = cnt[(size_t)i * 65 + 64];
     int a64;
-    const int a = allocate_wave(kk[i], C, c, c64, a64);
+    const int a = allocate_wave(kk[i], C, c, c64, a64, adjust != 0);
     alloc[(size_t)i * 65 + lane] = lane <= C ? a : 0;
     if (lane == 0) alloc[(size_t)i * 65 + 64] = C == 64 ? a64 : 0;
 }
@@ -274,7 +278,7 @@ struct Layout {
     size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2];
     size_t cons_tok, phr_off, nphr, ftok, sfl, bloom, rowlists, conskeys, counters;
     size_t hist_token, hist_backptr;
-    size_t fin_tokens, fin_len, fin_score, fin_status;
+    size_t fin_tokens, fin_len, fin_score, fin_status, all_finished;
     size_t total;
 };
 
@@ -311,6 +315,7 @@ Layout make_layout(size_t B, size_t k, size_t N)
     L.fin_len = take(B * sizeof(int32_t));
     L.fin_score = take(B * sizeof(float));
     L.fin_status = take(B * sizeof(int32_t));
+    L.all_finished = take(B);
     L.total = off;
     return L;
 }
@@ -331,6 +336,9 @@ struct dba_ctx {
     int max_phrases;
     int steps;
     int fused;                          // DBA_OPT_FUSED_LAUNCH
+    int adjust;                         // DBA_OPT_ADJUSTMENT
+    int normalize;                      // DBA_OPT_NORMALIZE_FINISHED
+    float prune;                        // DBA_OPT_PRUNE_THRESHOLD (< 0: off)
     size_t dyn_smem;
     unsigned char *ws;
     Layout L;
@@ -463,6 +471,9 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->L = L;
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->fused = 0;
+    c->adjust = 1;
+    c->normalize = 0;
+    c->prune = -1.0f;
     int npad = kWave;
     while (npad < k * (max_phrases + 2)) npad <<= 1;
     c->dyn_smem = (size_t)npad * sizeof(u64);
@@ -485,7 +496,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
             B, k, at<int32_t>(c, L.phr_off), at<int32_t>(c, L.nphr), at<float>(c, L.score[0]),
             at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]), at<int32_t>(c, L.len[0]),
             at<uint8_t>(c, L.fin[0]), at<u64>(c, L.inc[0]), at<int32_t>(c, L.nxt[0]),
-            at<unsigned int>(c, L.counters));
+            at<unsigned int>(c, L.counters), at<uint8_t>(c, L.all_finished));
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);   // host tables are freed on return
@@ -515,6 +526,9 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.met_bits = c->met_bits;
     p.tok_bits = c->tok_bits;
     p.first_step = c->steps == 0 ? 1 : 0;
+    p.adjust = c->adjust;
+    p.normalize = c->normalize;
+    p.prune = c->prune;
     p.logp = logp_dev;
     p.score_cur = at<float>(c, L.score[cur]);
     p.met_cur = at<u64>(c, L.met[cur]);
@@ -546,6 +560,7 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     const size_t hrow = (size_t)c->steps * c->B * c->k;
     p.hist_token = at<int32_t>(c, L.hist_token) + hrow;
     p.hist_backptr = at<int32_t>(c, L.hist_backptr) + hrow;
+    p.all_finished = at<uint8_t>(c, L.all_finished);
 
     // 4 wavefronts per row, 4 float4 per lane and tile: 1280 rows x 4 waves fill the 1024 SIMDs five
     // deep with two 4 KB tiles in flight per wave (measured best on MI355X at V = 32000)
@@ -571,7 +586,8 @@ DBA_API int dba_finalize(dba_ctx *c, int32_t *out_tokens_host, int32_t *out_len_
     const Layout &L = c->L;
     const int cur = c->steps & 1;
     dba_finalize_kernel<<<(c->B + 63) / 64, 64, 0, c->stream>>>(
-        c->B, c->k, c->steps, c->N, c->pad_id, at<int32_t>(c, L.hist_token), at<int32_t>(c, L.hist_backptr),
+        c->B, c->k, c->steps, c->N, c->pad_id, c->normalize, at<int32_t>(c, L.hist_token),
+        at<int32_t>(c, L.hist_backptr),
         at<float>(c, L.score[cur]), at<u64>(c, L.met[cur]), at<int32_t>(c, L.len[cur]),
         at<uint8_t>(c, L.fin[cur]), at<int32_t>(c, L.fin_tokens), at<int32_t>(c, L.fin_len),
         at<float>(c, L.fin_score), at<int32_t>(c, L.fin_status));
@@ -623,21 +639,36 @@ DBA_API int dba_get_state(dba_ctx *c, float *score_host, uint64_t *met_mask_host
 
 DBA_API int dba_steps_done(const dba_ctx *c) { return c ? c->steps : DBA_EINVAL; }
 
-DBA_API int dba_set_option(dba_ctx *c, int option, int value)
+DBA_API int dba_set_option(dba_ctx *c, int option, double value)
 {
     if (!c) return DBA_EINVAL;
     if (c->steps != 0) return fail(c, DBA_ESTATE, "dba_set_option: options are fixed once the first step is taken");
+    if (value != value) return fail(c, DBA_EINVAL, "dba_set_option: the value is not a number");
     switch (option) {
-        case DBA_OPT_FUSED_LAUNCH: c->fused = value ? 1 : 0; return DBA_OK;
+        case DBA_OPT_FUSED_LAUNCH: c->fused = value != 0.0 ? 1 : 0; return DBA_OK;
+        case DBA_OPT_ADJUSTMENT: c->adjust = value != 0.0 ? 1 : 0; return DBA_OK;
+        case DBA_OPT_NORMALIZE_FINISHED: c->normalize = value != 0.0 ? 1 : 0; return DBA_OK;
+        case DBA_OPT_PRUNE_THRESHOLD: c->prune = value < 0.0 ? -1.0f : (float)value; return DBA_OK;
         default: return fail(c, DBA_EINVAL, "dba_set_option: unknown option %d", option);
     }
+}
+
+DBA_API int dba_get_finished(dba_ctx *c, uint8_t *all_finished_host)
+{
+    if (!c) return DBA_EINVAL;
+    if (!all_finished_host) return fail(c, DBA_EINVAL, "dba_get_finished: the output pointer is NULL");
+    hipError_t e = hipMemcpyAsync(all_finished_host, at<uint8_t>(c, c->L.all_finished), (size_t)c->B,
+                                  hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_get_finished: HIP error: %s", hipGetErrorString(e));
+    return DBA_OK;
 }
 
 DBA_API void dba_destroy(dba_ctx *c) { delete c; }
 
 DBA_API const char *dba_last_error(const dba_ctx *c) { return c ? c->err : g_init_error; }
 
-DBA_API int dba_debug_allocate(int n_cases, const int32_t *k_host, const int32_t *C_host, const int32_t *cnt_host,
+DBA_API int dba_debug_allocate(int n_cases, int adjust, const int32_t *k_host, const int32_t *C_host, const int32_t *cnt_host,
                        int32_t *alloc_host, void *scratch_dev, size_t scratch_bytes, void *hip_stream)
 {
     if (n_cases < 1 || !k_host || !C_host || !cnt_host || !alloc_host || !scratch_dev)
@@ -656,7 +687,7 @@ DBA_API int dba_debug_allocate(int n_cases, const int32_t *k_host, const int32_t
     if (e == hipSuccess) e = hipMemcpyAsync(d_C, C_host, n * 4, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipMemcpyAsync(d_cnt, cnt_host, n * 65 * 4, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) {
-        dba_allocate_kernel<<<dim3((unsigned)n_cases), dim3(kWave), 0, s>>>(n_cases, d_k, d_C, d_cnt, d_alloc);
+        dba_allocate_kernel<<<dim3((unsigned)n_cases), dim3(kWave), 0, s>>>(n_cases, adjust, d_k, d_C, d_cnt, d_alloc);
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipMemcpyAsync(alloc_host, d_alloc, n * 65 * 4, hipMemcpyDeviceToHost, s);

@@ -34,6 +34,9 @@ struct StepParams {
     int met_bits;                     // width of the bank field in the packed selection key
     int tok_bits;                     // width of the token field of a coordinate: (h << tok_bits) | w
     int first_step;                   // 1: the beam is the initial one (only slot 0 of a sentence is live)
+    int adjust;                       // 0: bank sizes stay at the base split (Sec. 5)
+    int normalize;                    // 1: a hypothesis completing now is stored with sum / length (Sec. 4)
+    float prune;                      // >= 0: threshold pruning against the best completed hypothesis (Sec. 4)
     const float *logp;                // [B,k,V]
     // beam before the step
     const float *score_cur;           // [B,k]  (-inf: empty slot)
@@ -68,6 +71,7 @@ struct StepParams {
     float *out_score;
     uint8_t *out_flags;
     int32_t *hist_token, *hist_backptr;   // row t of the history, [B,k]
+    uint8_t *all_finished;            // [B] 1: the new beam is not empty and every hypothesis on it is completed
 };
 
 // constraints of one sentence: token ids phrase after phrase, phrase p = tok[poff[p] .. poff[p+1])
@@ -428,7 +432,8 @@ __device__ __forceinline__ int expandable_entry(int P, int nmet, u64 inc, int ip
 // more slots than candidates, in ascending order, keep what they can fill and
 // pass the rest to banks with spare candidates, nearest first, the higher
 // neighbour before the lower, as much as each can take.
-__device__ __forceinline__ int allocate_wave(int k, int C, int c, int c64, int &a64)
+// adjust = false (Sec. 5): the base split stays; a bank keeps only the slots it can fill.
+__device__ __forceinline__ int allocate_wave(int k, int C, int c, int c64, int &a64, bool adjust)
 {
     const int lane = lane_id();
     const int base = k / (C + 1);
@@ -437,6 +442,10 @@ __device__ __forceinline__ int allocate_wave(int k, int C, int c, int c64, int &
     a64 = (C == 64) ? base + rem : 0;
     if (lane > C) c = 0;
     if (C < 64) c64 = 0;
+    if (!adjust) {
+        a64 = min(a64, c64);
+        return min(a, c);
+    }
 
     u64 donors = __ballot(a > c);                         // fixed before the hand-outs begin:
     bool donor64 = a64 > c64;                             // a receiver never becomes a donor
@@ -705,7 +714,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         const int c = sm.cnt[lane];
         const int c64 = sm.cnt[kMaxCons];
         int a64;
-        const int a = allocate_wave(k, C, c, c64, a64);
+        const int a = allocate_wave(k, C, c, c64, a64, p.adjust != 0);
         sm.alloc[lane] = a;
         if (lane == 0) sm.alloc[kMaxCons] = a64;
         const int cc = lane <= C ? c : 0;
@@ -818,16 +827,33 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             fin2 = (pfin || token == p.eos_id) ? 1 : 0;
             length = pfin ? hs.len : hs.len + 1;
             flags = fin2;
+            // Sec. 4: a hypothesis that completes now is kept with its score per word (one fp32
+            // division, the length counts end-of-sentence); it competed with its raw sum above
+            if (p.normalize && fin2 && !pfin) score = __fdiv_rn(score, (float)length);
         }
-        if (lane < k) {
-            const size_t o = (size_t)b * k + lane;
+        // Sec. 4 / Sec. 6.3: hypotheses, completed or not, below (best completed - threshold) leave
+        // the beam; the others close ranks
+        bool keep = live;
+        int slot = lane, nlive = nsel;
+        if (p.prune >= 0.0f) {
+            float best = (live && fin2) ? score : -INFINITY;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) best = fmaxf(best, __shfl_xor(best, d, kWave));
+            if (best > -INFINITY) keep = live && score >= best - p.prune;
+            const u64 km = __ballot(keep);
+            slot = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(km >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)km, 0u));
+            nlive = __popcll(km);
+        }
+        const u64 open = __ballot(keep && !fin2);
+        if (keep) {
+            const size_t o = (size_t)b * k + slot;
             p.score_nxt[o] = score;
             p.met_nxt[o] = met2;
             p.inc_nxt[o] = inc2;
             p.ipq_nxt[o] = ipq2;
             p.nxt_nxt[o] = nxt2;
             p.len_nxt[o] = length;
-            p.fin_nxt[o] = (uint8_t)(fin2 | ((live && !fin2 && __popcll(met2) < C) ? kFinEosBlocked : 0));
+            p.fin_nxt[o] = (uint8_t)(fin2 | ((!fin2 && __popcll(met2) < C) ? kFinEosBlocked : 0));
             p.hist_token[o] = token;
             p.hist_backptr[o] = parent;
             if (p.out_token) p.out_token[o] = token;
@@ -835,6 +861,23 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             if (p.out_score) p.out_score[o] = score;
             if (p.out_flags) p.out_flags[o] = flags;
         }
+        if (lane >= nlive && lane < k) {                  // empty slots
+            const size_t o = (size_t)b * k + lane;
+            p.score_nxt[o] = -INFINITY;
+            p.met_nxt[o] = 0;
+            p.inc_nxt[o] = 0;
+            p.ipq_nxt[o] = -1;
+            p.nxt_nxt[o] = -1;
+            p.len_nxt[o] = 0;
+            p.fin_nxt[o] = 0;
+            p.hist_token[o] = p.pad_id;
+            p.hist_backptr[o] = -1;
+            if (p.out_token) p.out_token[o] = p.pad_id;
+            if (p.out_backptr) p.out_backptr[o] = -1;
+            if (p.out_score) p.out_score[o] = -INFINITY;
+            if (p.out_flags) p.out_flags[o] = 2;
+        }
+        if (lane == 0) p.all_finished[b] = (uint8_t)((nlive > 0 && open == 0) ? 1 : 0);   // stopping test, Sec. 4
     }
 }
 

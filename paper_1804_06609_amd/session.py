@@ -58,6 +58,12 @@ class Session:
         _b.dba_get_state(self.ctx, **st)
         return st
 
+    def finished(self) -> np.ndarray:
+        """[B] uint8: 1 where every hypothesis on the sentence's beam is completed (synchronises)."""
+        done = np.empty(self.B, np.uint8)
+        _b.dba_get_finished(self.ctx, done)
+        return done
+
     def finalize(self):
         toks = np.empty((self.B, self.N), np.int32)
         ln = np.empty(self.B, np.int32)

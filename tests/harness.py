@@ -30,15 +30,23 @@ def _first_diff(name, got, want, t, sent_ids):
 
 def run_parity(wl: si.Workload, T: Optional[int] = None, oracle_sentences: Optional[Sequence[int]] = None,
                check_state_every: int = 1, check_invariants: bool = True, progress: str = "",
-               options: Optional[dict] = None):
+               options: Optional[dict] = None, adjust: bool = True, normalize: bool = False,
+               prune: Optional[float] = None):
     """Runs T steps of wl on the GPU and on the oracle (all sentences, or the sampled ones) and
-    compares every step.  Returns the session's finalize() result after checking it too."""
+    compares every step.  Returns the session's finalize() result after checking it too.
+    adjust / normalize / prune switch the same variant on both sides (Sec. 5; Sec. 4)."""
+    import paper_1804_06609_amd as dba
+    options = dict(options or {})
+    options[dba.DBA_OPT_ADJUSTMENT] = int(adjust)
+    options[dba.DBA_OPT_NORMALIZE_FINISHED] = int(normalize)
+    options[dba.DBA_OPT_PRUNE_THRESHOLD] = -1.0 if prune is None else prune
     T = wl.T if T is None else T
     B, k, V = wl.B, wl.k, wl.V
     sent = list(range(B)) if oracle_sentences is None else sorted(oracle_sentences)
     toks, poff, soff = wl.csr()
     ses = Session(B, k, V, T, wl.eos_id, wl.pad_id, toks, poff, soff, options=options)
-    ob = oracle.BatchBeam(k, V, wl.constraints, wl.eos_id, wl.pad_id, sentences=sent)
+    ob = oracle.BatchBeam(k, V, wl.constraints, wl.eos_id, wl.pad_id, sentences=sent, adjust=adjust,
+                          normalize_finished=normalize, prune_threshold=prune)
     host = torch.empty((B, k, V), dtype=torch.float32, pin_memory=True)
     dev = torch.empty((B, k, V), dtype=torch.float32, device="cuda")
     for t in range(T):
@@ -59,8 +67,10 @@ def run_parity(wl: si.Workload, T: Optional[int] = None, oracle_sentences: Optio
             _first_diff("state.inprog_pos", st["inprog_pos"][sent], ob.stacked("iq"), t, sent)
             _first_diff("state.length", st["length"][sent], ob.stacked("len"), t, sent)
             _first_diff("state.flags", st["flags"][sent], ob.stacked("flags"), t, sent)
+        done = ses.finished()
+        assert done[sent].tolist() == [bm.all_finished for bm in ob.beams], f"all-finished flags, step {t}"
         if check_invariants:
-            check_step_properties(wl, g_tok, g_bp, g_sc, g_fl)
+            check_step_properties(wl, g_tok, g_bp, g_sc, g_fl, ordered=not normalize)
         if progress and (t % 10 == 9 or t == T - 1):
             print(f"  {progress}: step {t + 1}/{T} ok", flush=True)
     fin = ses.finalize()
@@ -71,7 +81,7 @@ def run_parity(wl: si.Workload, T: Optional[int] = None, oracle_sentences: Optio
     return fin
 
 
-def check_step_properties(wl, tok, bp, sc, fl):
+def check_step_properties(wl, tok, bp, sc, fl, ordered=True):
     """Properties of one step's output that hold for every sentence at any size."""
     live = fl != 2
     assert ((sc == -np.inf) == ~live).all()
@@ -81,7 +91,7 @@ def check_step_properties(wl, tok, bp, sc, fl):
     # live slots come first and are in non-increasing score order
     assert (live[:, :-1] >= live[:, 1:]).all()
     s2 = np.where(live, sc, -np.inf)
-    assert (s2[:, :-1] >= s2[:, 1:]).all()
+    assert not ordered or (s2[:, :-1] >= s2[:, 1:]).all()
     # no coordinate twice in a beam
     flat = np.where(live, bp.astype(np.int64) * wl.V + tok, -1 - np.arange(wl.k)[None, :])
     srt = np.sort(flat, axis=1)

@@ -54,14 +54,15 @@ def test_allocation_device_matches_oracle(torch_gpu):
     cnt = np.zeros((n, 65), np.int32)
     for i, c in enumerate(cases):
         cnt[i, :len(c[2])] = c[2]
-    alloc = np.full((n, 65), -7, np.int32)
     scratch = torch_gpu.empty(n * 132 * 4, dtype=torch_gpu.uint8, device="cuda")
-    dba.dba_debug_allocate(kk, CC, cnt, alloc, scratch.data_ptr(), scratch.numel(),
-                           torch_gpu.cuda.current_stream().cuda_stream)
-    for i, (k, C, c) in enumerate(cases):
-        want = oracle.allocate(k, c)
-        assert list(alloc[i, :C + 1]) == list(want), (k, C, c, alloc[i, :C + 1], want)
-        assert (alloc[i, C + 1:] == 0).all()
+    for adjust in (True, False):         # Sec. 3.2, and the fixed split of Sec. 5
+        alloc = np.full((n, 65), -7, np.int32)
+        dba.dba_debug_allocate(kk, CC, cnt, alloc, scratch.data_ptr(), scratch.numel(),
+                               torch_gpu.cuda.current_stream().cuda_stream, adjust=adjust)
+        for i, (k, C, c) in enumerate(cases):
+            want = oracle.allocate(k, c, adjust=adjust)
+            assert list(alloc[i, :C + 1]) == list(want), (adjust, k, C, c, alloc[i, :C + 1], want)
+            assert (alloc[i, C + 1:] == 0).all()
 
 
 def test_wave_selection_primitives(torch_gpu):
@@ -142,6 +143,48 @@ def test_one_launch_form_small(torch_gpu, seed):
 def test_one_launch_form_config2(torch_gpu):
     from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
     _harness().run_parity(si.make_config(2, T=15), options={DBA_OPT_FUSED_LAUNCH: 1})
+
+
+VARIANTS = [
+    dict(adjust=False),
+    dict(normalize=True),
+    dict(prune=3.0),
+    dict(normalize=True, prune=20.0),          # the set-up of Sec. 4
+    dict(adjust=False, normalize=True, prune=0.0),
+]
+
+
+@pytest.mark.parametrize("vi", range(len(VARIANTS)))
+@pytest.mark.parametrize("seed", range(6))
+def test_variants_small(torch_gpu, seed, vi):
+    """Sec. 5 (no adjustment), Sec. 4 (completed hypotheses hold score/length; threshold pruning;
+    the stopping test) on small odd shapes in which hypotheses complete early."""
+    rs = si.Stream(seed, 6)
+    B = rs.randint(1, 5)
+    k = [2, 5, 13, 20, 33, 64][seed % 6]
+    V = max(k + 3, [64, 257, 1001, 1023, 2050, 4099][(seed // 2) % 6])
+    T = rs.randint(8, 14)
+    wl = si.make_small(9300 + 10 * vi + seed, B, k, V, T, max_phrases=4, max_len=3, dup_prob=0.35)
+    wl.eos_switch = 3
+    wl.eos_high = [0.5, 3.0][seed % 2]
+    _harness().run_parity(wl, **VARIANTS[vi])
+
+
+def test_paper_setup_config2(torch_gpu):
+    """Config 2 shapes with the decoding set-up of Sec. 4: score per word for completed
+    hypotheses, pruning threshold 20; end-of-sentence becomes likely after a third of the run."""
+    wl = si.make_config(2, T=30)
+    wl.eos_switch = 10
+    _harness().run_parity(wl, normalize=True, prune=20.0)
+
+
+def test_gbs_simulation(torch_gpu):
+    """Sec. 5: beam b(C+1), adjustment off - C = 3 single-token constraints, b = 5."""
+    B, V, T, b, C = 6, 8000, 25, 5, 3
+    cons = si.fixed_total_constraints(53, B, V, C, max_len=1)
+    wl = si.Workload(B=B, k=b * (C + 1), V=V, T=T, seed=53, constraints=cons,
+                     boost_tokens=[[w for p in s for w in p] for s in cons], boost_prob=0.05)
+    _harness().run_parity(wl, adjust=False)
 
 
 def test_call_order_errors(torch_gpu):
