@@ -31,10 +31,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
-# HBM bytes per launch (fetched + written) of the step kernel on the config-4 workload, from the
+# HBM bytes per step (fetched + written by its two launches) on the config-4 workload, from the
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled against a plain copy);
-# None whenever the kernel has changed since those counters were taken.
-TRAFFIC_BYTES_PER_LAUNCH = None
+# None whenever a kernel has changed since those counters were taken.
+TRAFFIC_BYTES_PER_LAUNCH = 168413894
 
 
 def build_workload(cfg: int, cons_tokens):
