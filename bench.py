@@ -115,6 +115,9 @@ def main():
                          "sentence (the paper's O(1)-in-C claim), one JSON line")
     ap.add_argument("--fused", action="store_true",
                     help="time the one-launch form of the step (DBA_OPT_FUSED_LAUNCH) instead of the default")
+    ap.add_argument("--logp-format", choices=["f32", "f16", "bf16"], default="f32",
+                    help="element type of the resident log-prob tensors (default f32, the headline workload); "
+                         "16-bit tensors halve the algorithmic bytes, the sums stay fp32")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain device copy of one input tensor (known size) a few times, so "
                          "that a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
@@ -145,7 +148,14 @@ def main():
 
     # resident inputs
     host = [wl.logp(t) for t in range(R)]
-    dev = [torch.from_numpy(h).cuda() for h in host]
+    esize = 4
+    if args.logp_format == "f32":
+        dev = [torch.from_numpy(h).cuda() for h in host]
+    else:
+        tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[args.logp_format]
+        bits = [si.narrow16(h, args.logp_format) for h in host]
+        dev = [torch.from_numpy(x.view(np.int16)).cuda().view(tdt) for x in bits]
+        esize = 2
     torch.cuda.synchronize()
 
     from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
@@ -157,7 +167,7 @@ def main():
     live_rows = 0
     for g in range(W, W + K):
         live_rows += B * (1 if g % dlen == 0 else k)
-    bytes_total = 4.0 * live_rows * V
+    bytes_total = float(esize) * live_rows * V
     launches = K
     achieved = bytes_total / launches / (ev_ms * 1e-3 / launches) / 1e9
 
@@ -178,7 +188,7 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": f"config{args.config}: B={B} k={k} V={V}, {ctok_desc} constraint tokens/sentence, "
-                        f"decodes of {dlen} steps, {R} rotating resident tensors",
+                        f"decodes of {dlen} steps, {R} rotating resident {args.logp_format} tensors",
             "batch": B, "beam": k, "vocab": V, "decode_len": dlen,
         },
         "selection_GBps": bytes_total / wall_s / 1e9,
@@ -189,10 +199,10 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": TRAFFIC_BYTES_PER_LAUNCH
-            if (args.config == 4 and args.cons_tokens is None and not args.fused) else None,
-            "kernel": "dba_stream_kernel<4> + dba_merge_kernel (the two launches of one step, back to back)"
+            if (args.config == 4 and args.cons_tokens is None and not args.fused and esize == 4) else None,
+            "kernel": "dba_stream_kernel + dba_merge_kernel (the two launches of one step, back to back)"
                       if not args.fused else
-                      "dba_step_fused_kernel<4> (one launch per step: stream phase + merge phase)",
+                      "dba_step_fused_kernel (one launch per step: stream phase + merge phase)",
             "us_per_launch": ev_ms * 1e3 / launches,
             "algorithmic_bytes_per_launch": bytes_total / launches,
         },
@@ -203,7 +213,7 @@ def main():
         for i in range(4):
             dst.copy_(dev[i % R])        # reads 4*B*k*V bytes, writes as many
         torch.cuda.synchronize()
-        out["copy_probe_bytes_each_way"] = 4 * B * k * V
+        out["copy_probe_bytes_each_way"] = esize * B * k * V
 
     if not args.no_cpu_baseline:
         import oracle
@@ -211,6 +221,8 @@ def main():
         S = 12 if args.config == 4 else 4
         ob = oracle.BatchBeam(k, V, wl.constraints, wl.eos_id, wl.pad_id)
         ses = Session(B, k, V, S, wl.eos_id, wl.pad_id, toks, poff, soff)
+        if esize == 2:
+            host = [oracle.widen16(x, args.logp_format) for x in bits]
         t0 = time.perf_counter()
         for t in range(S):
             ob.step(host[t % R], threads=threads)

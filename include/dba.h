@@ -111,6 +111,19 @@ DBA_API int dba_step(dba_ctx *ctx, const float *logp_dev, int32_t *out_token_dev
              int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev);
 
 /*
+ * dba_step for a decoder that hands over its log-probs in another element type.  logp_dev is
+ * device [B,k,V] of that type, row-major, aligned to the element size (rows need no further
+ * alignment).  A 16-bit log-prob is widened to fp32 exactly (both conversions are exact) and the
+ * score is then the same single fp32 addition parent score + logp; everything else is dba_step.
+ * The formats may change from call to call.  DBA_EINVAL for an unknown format.
+ */
+#define DBA_LOGP_F32 0  /* fp32 (what dba_step takes)   */
+#define DBA_LOGP_F16 1  /* IEEE binary16                */
+#define DBA_LOGP_BF16 2 /* bfloat16                     */
+DBA_API int dba_step_fmt(dba_ctx *ctx, const void *logp_dev, int logp_format, int32_t *out_token_dev,
+                         int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev);
+
+/*
  * End of Alg. 1 with Sec. 3.3 and the length normalisation of Sec. 4: for each
  * sentence the completed hypothesis (end-of-sentence generated, hence all
  * constraints met) with the best score/length, traced back through the

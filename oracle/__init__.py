@@ -70,6 +70,18 @@ def allocate(k: int, cnt: Sequence[int], adjust: bool = True) -> np.ndarray:
     return out
 
 
+def widen16(bits: np.ndarray, fmt: str) -> np.ndarray:
+    """16-bit log-probs (uint16 bit patterns of IEEE binary16 "f16" or bfloat16 "bf16") as the
+    fp32 values they stand for; both conversions are exact.  The step then computes, as always,
+    one fp32 addition prev + logp on the widened value."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    if fmt == "f16":
+        return bits.view(np.float16).astype(np.float32)
+    if fmt == "bf16":
+        return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    raise ValueError(f"unknown 16-bit format {fmt!r}")
+
+
 def _phrase_arrays(phrases: Sequence[Sequence[int]]):
     off = [0]
     tok: List[int] = []

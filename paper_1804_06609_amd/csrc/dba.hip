@@ -18,11 +18,13 @@ using namespace dba;
 // ---------------------------------------------------------------------------
 // Stream phase of one beam row by one workgroup of blockDim.x/64 waves: leaves the row's sorted
 // top keys in p.rowlists and the keys of its constraint tokens in p.conskeys.
-// U = float4 loads each lane keeps in flight per tile.  PUBLISH: the two results are written
-// with device-scope atomic stores, for readers in other workgroups of the same launch.
-template <int U, bool PUBLISH>
+// U = 16-byte loads each lane keeps in flight per tile; FMT = element type of the log-probs.
+// PUBLISH: the two results are written with device-scope atomic stores, for readers in other
+// workgroups of the same launch.
+template <int U, int FMT, bool PUBLISH>
 __device__ __forceinline__ void stream_phase(const StepParams &p, int row, StreamSmem &sm)
 {
+    typedef typename Logp<FMT>::elem_t elem_t;
     const int b = row / p.k;
     const int h = row - b * p.k;
     const int lane = lane_id();
@@ -46,8 +48,8 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
         g_ftok = p.first_tok[(size_t)b * kMaxCons + lane];
         g_sfl = p.same_first_lower[(size_t)b * kMaxCons + lane];
     }
-    const float *__restrict__ logp_row = p.logp + (size_t)row * (size_t)p.V;
-    RowStream<U> rs;
+    const elem_t *__restrict__ logp_row = static_cast<const elem_t *>(p.logp) + (size_t)row * (size_t)p.V;
+    RowStream<U, FMT> rs;
     const bool known_empty = p.first_step && h != 0;   // decoder-init leaves slots 1.. empty
     if (!known_empty) rs.begin(logp_row, p.V, wave, nwaves);
     if (threadIdx.x == 0) sm.thr = ord_from_float(-INFINITY);
@@ -70,7 +72,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
         if (gatherer)
             cw = expandable_entry(g_P, __popcll(g_met), g_inc, g_ipq < 0 ? -1 : (g_ipq >> 8),
                                   g_ipq < 0 ? 0 : (g_ipq & 255), g_nxt, g_ftok, g_sfl, cbank);
-        const float cx = cw >= 0 ? logp_row[cw] : -INFINITY;
+        const float cx = cw >= 0 ? Logp<FMT>::widen_one(logp_row[cw]) : -INFINITY;
         // Sec. 3.3: no end-of-sentence before all constraints are met
         const int eos_block = (fin & kFinEosBlocked) ? p.eos_id : -1;
         rs.run(prev, eos_block, code_base, p.k, wave, nwaves, sm, st);
@@ -101,11 +103,11 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
 }
 
 // Two-launch form, first launch.  Grid: one workgroup per beam row.
-template <int U>
+template <int U, int FMT>
 __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
 {
     __shared__ StreamSmem sm;
-    stream_phase<U, false>(p, (int)blockIdx.x, sm);
+    stream_phase<U, FMT, false>(p, (int)blockIdx.x, sm);
 }
 
 // One-launch form.  Grid: one workgroup (256 threads) per beam row.  Every workgroup streams
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
 // arrival counter with a device-scope atomic.  Whoever reads k-1 there knows all k rows have
 // arrived and reads them with device-scope atomic loads (which bypass the non-coherent
 // caches).  No workgroup ever waits for another.
-template <int U>
+template <int U, int FMT>
 __global__ __launch_bounds__(kBlock) void dba_step_fused_kernel(const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(kBlock) void dba_step_fused_kernel(const StepParams
 
     const int row = (int)blockIdx.x;
     const int b = row / p.k;
-    stream_phase<U, true>(p, row, *reinterpret_cast<StreamSmem *>(raw));
+    stream_phase<U, FMT, true>(p, row, *reinterpret_cast<StreamSmem *>(raw));
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's published stores are done
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -512,10 +514,19 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
 DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, int32_t *out_backptr_dev,
              float *out_score_dev, uint8_t *out_flags_dev)
 {
+    return dba_step_fmt(c, logp_dev, DBA_LOGP_F32, out_token_dev, out_backptr_dev, out_score_dev, out_flags_dev);
+}
+
+DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int32_t *out_token_dev,
+                         int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev)
+{
     if (!c) return DBA_EINVAL;
     if (!logp_dev) return fail(c, DBA_EINVAL, "dba_step: logp_dev is NULL");
-    if (reinterpret_cast<uintptr_t>(logp_dev) % 4 != 0)
-        return fail(c, DBA_EINVAL, "dba_step: logp_dev must be 4-byte aligned");
+    if (logp_format != DBA_LOGP_F32 && logp_format != DBA_LOGP_F16 && logp_format != DBA_LOGP_BF16)
+        return fail(c, DBA_EINVAL, "dba_step: unknown log-prob format %d", logp_format);
+    const unsigned elem = logp_format == DBA_LOGP_F32 ? 4u : 2u;
+    if (reinterpret_cast<uintptr_t>(logp_dev) % elem != 0)
+        return fail(c, DBA_EINVAL, "dba_step: logp_dev must be aligned to its element size (%u bytes)", elem);
     if (c->steps >= c->N) return fail(c, DBA_ESTATE, "dba_step: all N=%d steps have been taken", c->N);
 
     const int cur = c->steps & 1, nxt = cur ^ 1;
@@ -562,13 +573,21 @@ DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, 
     p.hist_backptr = at<int32_t>(c, L.hist_backptr) + hrow;
     p.all_finished = at<uint8_t>(c, L.all_finished);
 
-    // 4 wavefronts per row, 4 float4 per lane and tile: 1280 rows x 4 waves fill the 1024 SIMDs five
-    // deep with two 4 KB tiles in flight per wave (measured best on MI355X at V = 32000)
+    // 4 wavefronts per row, 4 loads of 16 bytes per lane and tile: 1280 rows x 4 waves fill the 1024 SIMDs
+    // five deep with two 4 KB tiles in flight per wave (measured best on MI355X at V = 32000)
     const dim3 grid((unsigned)(c->B * c->k)), block(kBlock);
     if (c->fused) {
-        dba_step_fused_kernel<kTileLoads><<<grid, block, c->dyn_smem, c->stream>>>(p);
+        switch (logp_format) {
+            case DBA_LOGP_F16: dba_step_fused_kernel<kTileLoads, kFmtF16><<<grid, block, c->dyn_smem, c->stream>>>(p); break;
+            case DBA_LOGP_BF16: dba_step_fused_kernel<kTileLoads, kFmtBF16><<<grid, block, c->dyn_smem, c->stream>>>(p); break;
+            default: dba_step_fused_kernel<kTileLoads, kFmtF32><<<grid, block, c->dyn_smem, c->stream>>>(p); break;
+        }
     } else {
-        dba_stream_kernel<kTileLoads><<<grid, block, 0, c->stream>>>(p);
+        switch (logp_format) {
+            case DBA_LOGP_F16: dba_stream_kernel<kTileLoads, kFmtF16><<<grid, block, 0, c->stream>>>(p); break;
+            case DBA_LOGP_BF16: dba_stream_kernel<kTileLoads, kFmtBF16><<<grid, block, 0, c->stream>>>(p); break;
+            default: dba_stream_kernel<kTileLoads, kFmtF32><<<grid, block, 0, c->stream>>>(p); break;
+        }
         dba_merge_kernel<<<dim3((unsigned)c->B), block, c->dyn_smem, c->stream>>>(p);
     }
     const hipError_t e = hipGetLastError();

@@ -24,7 +24,10 @@ constexpr int kMaxBeam = 64;
 constexpr int kMaxCons = 64;          // constraint tokens (and phrases) per sentence
 constexpr int kBlock = 256;           // threads per workgroup
 constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kTileLoads = 4;         // float4 loads per lane and tile in the stream phase
+constexpr int kTileLoads = 4;         // 16-byte loads per lane and tile in the stream phase
+constexpr int kFmtF32 = 0;            // element type of the log-probs: fp32,
+constexpr int kFmtF16 = 1;            // IEEE binary16,
+constexpr int kFmtBF16 = 2;           // bfloat16 (the 16-bit types are widened exactly; the sum is fp32)
 constexpr int kFinFinished = 1;       // beam-state flag: the hypothesis has generated end-of-sentence
 constexpr int kFinEosBlocked = 4;     // beam-state flag: constraints unmet, end-of-sentence not allowed (Sec. 3.3)
 
@@ -37,7 +40,7 @@ struct StepParams {
     int adjust;                       // 0: bank sizes stay at the base split (Sec. 5)
     int normalize;                    // 1: a hypothesis completing now is stored with sum / length (Sec. 4)
     float prune;                      // >= 0: threshold pruning against the best completed hypothesis (Sec. 4)
-    const float *logp;                // [B,k,V]
+    const void *logp;                 // [B,k,V] in the element type the kernel is instantiated for
     // beam before the step
     const float *score_cur;           // [B,k]  (-inf: empty slot)
     const u64 *met_cur;               // [B,k]  bit i = constraint token i met
@@ -181,11 +184,7 @@ __device__ __forceinline__ void stage_candidates(RowTop &st, u64 *stage, int &cn
 }
 
 typedef float v4f __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ v4f neg_inf4()
-{
-    return v4f{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-}
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 // max of four finite-or-infinite floats in two instructions (the inputs are never NaN, so the
 // quieting moves a generic fmaxf would add are not needed)
@@ -197,11 +196,152 @@ __device__ __forceinline__ float max4(const v4f &x)
     return m;
 }
 
+// ---- element formats of the log-prob tensor ----------------------------------------------
+// A lane reads 16 bytes at a time: a "group" of G consecutive elements.  Every format answers
+// three questions about a group: may any of its elements reach the threshold (cheap, and
+// allowed to say yes too often, never no wrongly), what are its G elements as fp32 (exact), and
+// which single fp32 value is certainly not above the group's greatest element (for the
+// threshold floor).  The sum itself is always one fp32 addition prev + element.
+template <int FMT>
+struct Logp;
+
+template <>
+struct Logp<kFmtF32> {
+    static constexpr int G = 4;
+    typedef float elem_t;
+    typedef v4f vec_t;
+    struct Quick {};                                  // the quick test uses the fp32 threshold itself
+    static __device__ __forceinline__ vec_t neg_inf() { return v4f{-INFINITY, -INFINITY, -INFINITY, -INFINITY}; }
+    static __device__ __forceinline__ Quick quick(float, float) { return Quick{}; }
+    // rounding is monotone, so max(prev + x_i) == prev + max(x_i): one add decides for four
+    static __device__ __forceinline__ bool may_reach(const vec_t &x, float prev, float thr, const Quick &)
+    {
+        return prev + max4(x) >= thr;
+    }
+    static __device__ __forceinline__ void widen(const vec_t &x, float (&f)[G])
+    {
+        f[0] = x.x;
+        f[1] = x.y;
+        f[2] = x.z;
+        f[3] = x.w;
+    }
+    static __device__ __forceinline__ float some_element_at_most_max(const vec_t &x) { return max4(x); }
+    static __device__ __forceinline__ void drop(vec_t &x, int c)
+    {
+        if (c == 0) x.x = -INFINITY;
+        if (c == 1) x.y = -INFINITY;
+        if (c == 2) x.z = -INFINITY;
+        if (c == 3) x.w = -INFINITY;
+    }
+    static __device__ __forceinline__ float widen_one(elem_t e) { return e; }
+};
+
+// The two 16-bit formats are sign-magnitude like fp32, so among negative values a greater bit
+// pattern is a smaller number, and every non-negative pattern is below every negative one:
+// "element >= bound" for a negative bound is "pattern <= pattern of the bound" on unsigned
+// 16-bit integers.  The quick test therefore needs no conversion at all: the unsigned minimum
+// of the group's eight patterns (packed 16-bit minima) against one precomputed pattern.
+template <int FMT>
+struct Logp16 {
+    static constexpr int G = 8;
+    typedef uint16_t elem_t;
+    typedef v4u vec_t;
+    static constexpr uint32_t kNegInf = FMT == kFmtF16 ? 0xFC00u : 0xFF80u;
+    struct Quick {
+        uint32_t umax;    // greatest pattern whose sum still reaches the threshold (0xFFFF: test everything)
+    };
+    static __device__ __forceinline__ vec_t neg_inf()
+    {
+        const uint32_t w = kNegInf | (kNegInf << 16);
+        return v4u{w, w, w, w};
+    }
+    static __device__ __forceinline__ float widen_bits(uint32_t h)
+    {
+        if constexpr (FMT == kFmtBF16) return __uint_as_float(h << 16);
+        else return (float)__builtin_bit_cast(_Float16, (unsigned short)h);
+    }
+    static __device__ __forceinline__ float widen_one(elem_t e) { return widen_bits(e); }
+    // round-to-nearest pattern of a negative finite fp32 (a starting point only: quick() corrects it)
+    static __device__ __forceinline__ uint32_t narrow_bits(float d)
+    {
+        if constexpr (FMT == kFmtBF16) {
+            const uint32_t u = __float_as_uint(d);
+            return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+        } else {
+            return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)d);
+        }
+    }
+    // umax = the pattern of the smallest element x with fp32(prev + x) >= thr, found exactly: a
+    // rounded guess, then single steps while the next smaller element still reaches thr, then
+    // single steps back while the element itself does not.  If the steps run out on the way
+    // down, everything is tested (never wrong, only slower).  thr never decreases, so a value
+    // computed for an older thr stays valid.
+    static __device__ __forceinline__ Quick quick(float prev, float thr)
+    {
+        const float d = thr - prev;
+        if (!(d < 0.0f)) return Quick{0xFFFFu};
+        uint32_t u = narrow_bits(d);
+        if (u < 0x8000u) u = 0x8000u;
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (prev + widen_bits(u + 1u) >= thr) ++u;
+        if (prev + widen_bits(u + 1u) >= thr) return Quick{0xFFFFu};
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (u >= 0x8000u && !(prev + widen_bits(u) >= thr)) --u;
+        return Quick{u};
+    }
+    // unsigned minimum of the two 16-bit halves, both halves at once
+    static __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b)
+    {
+        uint32_t r;
+        asm("v_pk_min_u16 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+        return r;
+    }
+    static __device__ __forceinline__ uint32_t min_pattern(const vec_t &x)
+    {
+        const uint32_t c = pk_min_u16(pk_min_u16(x.x, x.y), pk_min_u16(x.z, x.w));
+        return min(c & 0xFFFFu, c >> 16);
+    }
+    static __device__ __forceinline__ bool may_reach(const vec_t &x, float, float, const Quick &q)
+    {
+        return min_pattern(x) <= q.umax;
+    }
+    static __device__ __forceinline__ void widen(const vec_t &x, float (&f)[G])
+    {
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = widen_bits(w[i] & 0xFFFFu);
+            f[2 * i + 1] = widen_bits(w[i] >> 16);
+        }
+    }
+    // the element with the smallest pattern: the greatest one if none is positive, else some
+    // positive one - in both cases an element of the group
+    static __device__ __forceinline__ float some_element_at_most_max(const vec_t &x)
+    {
+        return widen_bits(min_pattern(x));
+    }
+    static __device__ __forceinline__ void drop(vec_t &x, int c)
+    {
+        const uint32_t keep = (c & 1) ? 0x0000FFFFu : 0xFFFF0000u;
+        const uint32_t put = (c & 1) ? (kNegInf << 16) : kNegInf;
+        if ((c >> 1) == 0) x.x = (x.x & keep) | put;
+        if ((c >> 1) == 1) x.y = (x.y & keep) | put;
+        if ((c >> 1) == 2) x.z = (x.z & keep) | put;
+        if ((c >> 1) == 3) x.w = (x.w & keep) | put;
+    }
+};
+template <>
+struct Logp<kFmtF16> : Logp16<kFmtF16> {};
+template <>
+struct Logp<kFmtBF16> : Logp16<kFmtBF16> {};
+
 // The log-probs are read exactly once: non-temporal loads keep them from displacing
-// anything useful in the caches.
-template <int U>
-__device__ __forceinline__ void load_tile(const v4f *__restrict__ vec, int nv, int tile, int lane,
-                                          v4f (&x)[U])
+// anything useful in the caches.  nv = groups in the row's aligned body.
+template <int U, typename VEC>
+__device__ __forceinline__ void load_tile(const VEC *__restrict__ vec, int nv, int tile, int lane, VEC (&x)[U],
+                                          const VEC fill)
 {
     const int base = tile * (kWave * U);
     if (base + kWave * U <= nv) {
@@ -211,26 +351,21 @@ __device__ __forceinline__ void load_tile(const v4f *__restrict__ vec, int nv, i
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int i = base + u * kWave + lane;
-            x[u] = (i < nv) ? __builtin_nontemporal_load(vec + i) : neg_inf4();
+            x[u] = (i < nv) ? __builtin_nontemporal_load(vec + i) : fill;
         }
     }
 }
 
 // Sec. 3.3: while constraints are unmet the end-of-sentence entry does not exist.  rel = its
-// position inside the tile in floats (wave-uniform); the one lane holding it drops it.
-template <int U>
-__device__ __forceinline__ void block_eos(v4f (&x)[U], int rel, int lane)
+// position inside the tile in elements (wave-uniform); the one lane holding it drops it.
+template <int U, int FMT>
+__device__ __forceinline__ void block_eos(typename Logp<FMT>::vec_t (&x)[U], int rel, int lane)
 {
-    const int uu = rel / (4 * kWave), ln = (rel >> 2) & (kWave - 1), c = rel & 3;
+    constexpr int G = Logp<FMT>::G;
+    const int uu = rel / (G * kWave), ln = (rel / G) & (kWave - 1), c = rel & (G - 1);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        if (u == uu && lane == ln) {
-            if (c == 0) x[u].x = -INFINITY;
-            if (c == 1) x[u].y = -INFINITY;
-            if (c == 2) x[u].z = -INFINITY;
-            if (c == 3) x[u].w = -INFINITY;
-        }
-    }
+    for (int u = 0; u < U; ++u)
+        if (u == uu && lane == ln) Logp<FMT>::drop(x[u], c);
 }
 
 // LDS shared by the waves of one row's workgroup during the stream phase.
@@ -241,77 +376,83 @@ struct StreamSmem {
     unsigned int thr;                   // best bound any wave has published (order-preserving u32)
 };
 
-// One wave's share of one row: tiles wave, wave+nwaves, ... of 64*U float4 each.  Must be
-// called by every thread of the workgroup (it contains one barrier).
+// One wave's share of one row: tiles wave, wave+nwaves, ... of 64*U groups of 16 bytes each.
+// Must be called by every thread of the workgroup (it contains one barrier).
 //
-// s = prev + logp is a single fp32 add.  An element is looked at closely only if its sum can
-// still reach the row's k best (>=: a later element may tie the k-th score and win on the
-// coordinate).  Rounding is monotone, so max(prev + x_i) == prev + max(x_i): one add per
-// float4 decides whether any of its four elements needs a look.
+// s = prev + logp is a single fp32 add (a 16-bit log-prob is widened exactly first).  An
+// element is looked at closely only if its sum can still reach the row's k best (>=: a later
+// element may tie the k-th score and win on the coordinate); Logp<FMT>::may_reach decides that
+// for a whole 16-byte group at once.
 //
-// Thresholds.  (1) Every lane takes the maximum of its share of the wave's first tile; the
-// k-th greatest of all the workgroup's per-lane maxima is a floor: k different lanes hold an
-// element at least that large, so nothing below it can be among the row's k best.  (2) A wave
-// whose own list holds k entries uses the score of its k-th, publishes it into sm.thr (atomic
-// max on an order-preserving u32) and re-reads the workgroup's maximum once per tile.  Any
-// wave's bound holds for the whole row, so a stale value only lets a few more elements
-// through; it never drops one.  The row's best element is never below any bound, so it
-// always survives.
-template <int U>
+// Thresholds.  (1) Every lane takes an element of its share of the wave's first two tiles (the
+// greatest, where the format finds it cheaply); the k-th greatest of all the workgroup's
+// per-lane values is a floor: k different lanes hold an element at least that large, so nothing
+// below it can be among the row's k best.  (2) A wave whose own list holds k entries uses the
+// score of its k-th, publishes it into sm.thr (atomic max on an order-preserving u32) and
+// re-reads the workgroup's maximum once per tile.  Any wave's bound holds for the whole row, so
+// a stale value only lets a few more elements through; it never drops one.  The row's best
+// element is never below any bound, so it always survives.
+template <int U, int FMT>
 struct RowStream {
-    const float *row;
-    const v4f *vec;
+    typedef Logp<FMT> F;
+    typedef typename F::vec_t vec_t;
+    typedef typename F::elem_t elem_t;
+    static constexpr int G = F::G;
+
+    const elem_t *row;
+    const vec_t *vec;
     int V, head, nv, tail, ntiles;
-    v4f cur[U], nxt[U];
+    vec_t cur[U], nxt[U];
 
     // Issues the loads of this wave's first two tiles.  Needs nothing of the hypothesis, so it
     // runs before the beam state has arrived.
-    __device__ __forceinline__ void begin(const float *__restrict__ row_, int V_, int wave, int nwaves)
+    __device__ __forceinline__ void begin(const elem_t *__restrict__ row_, int V_, int wave, int nwaves)
     {
         const int lane = lane_id();
         row = row_;
         V = V_;
         const uintptr_t addr = reinterpret_cast<uintptr_t>(row);
-        head = (int)(((16u - (unsigned)(addr & 15u)) & 15u) >> 2);
+        head = (int)(((16u - (unsigned)(addr & 15u)) & 15u) / (unsigned)sizeof(elem_t));
         if (head > V) head = V;
-        nv = (V - head) >> 2;
-        tail = V - head - (nv << 2);
-        vec = reinterpret_cast<const v4f *>(row + head);
+        nv = (V - head) / G;
+        tail = V - head - nv * G;
+        vec = reinterpret_cast<const vec_t *>(row + head);
         ntiles = (nv + kWave * U - 1) / (kWave * U);
 #pragma unroll
-        for (int u = 0; u < U; ++u) nxt[u] = neg_inf4();
-        if (wave < ntiles) load_tile<U>(vec, nv, wave, lane, cur);
-        if (wave + nwaves < ntiles) load_tile<U>(vec, nv, wave + nwaves, lane, nxt);
+        for (int u = 0; u < U; ++u) nxt[u] = F::neg_inf();
+        if (wave < ntiles) load_tile<U>(vec, nv, wave, lane, cur, F::neg_inf());
+        if (wave + nwaves < ntiles) load_tile<U>(vec, nv, wave + nwaves, lane, nxt, F::neg_inf());
     }
 
     __device__ __forceinline__ void run(float prev, int eos_block, uint32_t flat_base, int kk, int wave,
                                         int nwaves, StreamSmem &sm, RowTop &st);
 };
 
-template <int U>
-__device__ __forceinline__ void RowStream<U>::run(float prev, int eos_block, uint32_t flat_base, int kk,
-                                                  int wave, int nwaves, StreamSmem &sm, RowTop &st)
+template <int U, int FMT>
+__device__ __forceinline__ void RowStream<U, FMT>::run(float prev, int eos_block, uint32_t flat_base, int kk,
+                                                       int wave, int nwaves, StreamSmem &sm, RowTop &st)
 {
     const int lane = lane_id();
+    constexpr int kTileElems = G * kWave * U;
     const int eos_rel0 = eos_block >= 0 ? eos_block - head : -1;   // position in the aligned body
     int tl = wave;
     uint32_t boot = ord_from_float(-INFINITY);
     if (tl < ntiles) {
         // both tiles already requested take part in the floor (8 KB per wave, 32 KB per row)
-        const int rel = eos_rel0 - tl * (4 * kWave * U);
-        if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(cur, rel, lane);
-        float lane_max = max4(cur[0]);
+        const int rel = eos_rel0 - tl * kTileElems;
+        if (eos_rel0 >= 0 && rel >= 0 && rel < kTileElems) block_eos<U, FMT>(cur, rel, lane);
+        float lane_max = F::some_element_at_most_max(cur[0]);
 #pragma unroll
         for (int u = 1; u < U; ++u) {
-            const float mu = max4(cur[u]);
+            const float mu = F::some_element_at_most_max(cur[u]);
             asm("v_max_f32 %0, %1, %2" : "=v"(lane_max) : "v"(lane_max), "v"(mu));
         }
         if (tl + nwaves < ntiles) {
-            const int rel2 = eos_rel0 - (tl + nwaves) * (4 * kWave * U);
-            if (eos_rel0 >= 0 && rel2 >= 0 && rel2 < 4 * kWave * U) block_eos<U>(nxt, rel2, lane);
+            const int rel2 = eos_rel0 - (tl + nwaves) * kTileElems;
+            if (eos_rel0 >= 0 && rel2 >= 0 && rel2 < kTileElems) block_eos<U, FMT>(nxt, rel2, lane);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const float mu = max4(nxt[u]);
+                const float mu = F::some_element_at_most_max(nxt[u]);
                 asm("v_max_f32 %0, %1, %2" : "=v"(lane_max) : "v"(lane_max), "v"(mu));
             }
         }
@@ -325,38 +466,39 @@ __device__ __forceinline__ void RowStream<U>::run(float prev, int eos_block, uin
     }
     st.floor = float_from_ord((uint32_t)__builtin_amdgcn_readlane((int)boot, kk - 1));
     st.thr = fmaxf(st.floor, kLowestFinite);
+    typename F::Quick quick = F::quick(prev, st.thr);
     u64 *stage = sm.stage[wave];
     int cnt = 0;
-    // one tile: test its U float4 groups, park what may belong to the top k
-    auto examine = [&](const v4f (&t)[U], int tile) {
+    // one tile: test its U groups, park what may belong to the top k
+    auto examine = [&](const vec_t (&t)[U], int tile) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const v4f x = t[u];
-            if (__any(prev + max4(x) >= st.thr)) {
-                const uint32_t flat0 = flat_base + (uint32_t)(head + 4 * ((tile * U + u) * kWave));
-                const float s0 = prev + x.x, s1 = prev + x.y, s2 = prev + x.z, s3 = prev + x.w;
-                const u64 m0 = __ballot(s0 >= st.thr);
-                if (m0) stage_candidates(st, stage, cnt, s0, m0, flat0, 4u, kk);
-                const u64 m1 = __ballot(s1 >= st.thr);
-                if (m1) stage_candidates(st, stage, cnt, s1, m1, flat0 + 1u, 4u, kk);
-                const u64 m2 = __ballot(s2 >= st.thr);
-                if (m2) stage_candidates(st, stage, cnt, s2, m2, flat0 + 2u, 4u, kk);
-                const u64 m3 = __ballot(s3 >= st.thr);
-                if (m3) stage_candidates(st, stage, cnt, s3, m3, flat0 + 3u, 4u, kk);
+            const vec_t x = t[u];
+            if (__any(F::may_reach(x, prev, st.thr, quick))) {
+                const uint32_t flat0 = flat_base + (uint32_t)(head + G * ((tile * U + u) * kWave));
+                float f[G];
+                F::widen(x, f);
+#pragma unroll
+                for (int c = 0; c < G; ++c) {
+                    const float sc = prev + f[c];
+                    const u64 mc = __ballot(sc >= st.thr);
+                    if (mc) stage_candidates(st, stage, cnt, sc, mc, flat0 + (uint32_t)c, (uint32_t)G, kk);
+                }
             }
         }
     };
     // after a tile: start the load that refills its registers (two tiles ahead) and make the
     // other buffer ready (end-of-sentence mask, freshest shared bound)
-    auto advance = [&](v4f (&done)[U], v4f (&next)[U], int next_tile) {
-        if (next_tile + nwaves < ntiles) load_tile<U>(vec, nv, next_tile + nwaves, lane, done);
+    auto advance = [&](vec_t (&done)[U], vec_t (&next)[U], int next_tile) {
+        if (next_tile + nwaves < ntiles) load_tile<U>(vec, nv, next_tile + nwaves, lane, done, F::neg_inf());
         if (next_tile < ntiles) {
-            const int rel = eos_rel0 - next_tile * (4 * kWave * U);
-            if (eos_rel0 >= 0 && rel >= 0 && rel < 4 * kWave * U) block_eos<U>(next, rel, lane);
+            const int rel = eos_rel0 - next_tile * kTileElems;
+            if (eos_rel0 >= 0 && rel >= 0 && rel < kTileElems) block_eos<U, FMT>(next, rel, lane);
             if (nwaves > 1) {
                 st.floor = fmaxf(st.floor, float_from_ord(sm.thr));
                 st.thr = fmaxf(st.thr, st.floor);
             }
+            quick = F::quick(prev, st.thr);
         }
     };
     while (tl < ntiles) {
@@ -368,17 +510,17 @@ __device__ __forceinline__ void RowStream<U>::run(float prev, int eos_block, uin
         advance(nxt, cur, tl + nwaves);
         tl += nwaves;
     }
-    // elements before the first / after the last 16-byte aligned group (rows whose
-    // length or start is not a multiple of four floats): at most 3 + 3, one per lane
+    // elements before the first / after the last 16-byte aligned group (rows whose length or
+    // start is not a multiple of one group): fewer than two groups, one element per lane
     if (wave == 0 && head + tail > 0) {
         const bool mine = lane < head + tail;
-        const int w = lane < head ? lane : head + (nv << 2) + (lane - head);
-        const float s = mine ? prev + row[w] : -INFINITY;
+        const int w = lane < head ? lane : head + nv * G + (lane - head);
+        const float s = mine ? prev + F::widen_one(row[w]) : -INFINITY;
         u64 m = __ballot(mine && (s >= st.thr) && (w != eos_block));
         while (m) {
             const int l = __ffsll((long long)m) - 1;
             m &= m - 1;
-            const int wl = l < head ? l : head + (nv << 2) + (l - head);
+            const int wl = l < head ? l : head + nv * G + (l - head);
             const uint32_t sbits = (uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(s), l);
             if (cnt + 1 > kStageCap) flush_stage(st, stage, cnt, kk);
             if (lane == 0) stage[cnt] = make_key_uniform(sbits, flat_base + (uint32_t)wl);

@@ -37,12 +37,18 @@ class Session:
         for opt, val in (options or {}).items():
             _b.dba_set_option(self.ctx, opt, val)
 
+    _FORMATS = {torch.float32: _b.DBA_LOGP_F32, torch.float16: _b.DBA_LOGP_F16, torch.bfloat16: _b.DBA_LOGP_BF16}
+
     def step(self, logp: torch.Tensor) -> None:
-        """Enqueue one step; logp is a device fp32 tensor [B,k,V], contiguous."""
-        assert logp.is_cuda and logp.dtype == torch.float32 and logp.is_contiguous()
+        """Enqueue one step; logp is a contiguous device tensor [B,k,V] of fp32, fp16 or bf16."""
+        assert logp.is_cuda and logp.dtype in self._FORMATS and logp.is_contiguous()
         assert tuple(logp.shape) == (self.B, self.k, self.V)
-        _b.dba_step(self.ctx, logp.data_ptr(), self.out_token.data_ptr(), self.out_backptr.data_ptr(),
-                    self.out_score.data_ptr(), self.out_flags.data_ptr())
+        if logp.dtype == torch.float32:
+            _b.dba_step(self.ctx, logp.data_ptr(), self.out_token.data_ptr(), self.out_backptr.data_ptr(),
+                        self.out_score.data_ptr(), self.out_flags.data_ptr())
+        else:
+            _b.dba_step_fmt(self.ctx, logp.data_ptr(), self._FORMATS[logp.dtype], self.out_token.data_ptr(),
+                            self.out_backptr.data_ptr(), self.out_score.data_ptr(), self.out_flags.data_ptr())
 
     def outputs(self):
         """(token, backptr, score, flags) of the last step as numpy arrays (synchronises)."""

@@ -207,6 +207,22 @@ class Workload:
         return out
 
 
+def narrow16(x: np.ndarray, fmt: str) -> np.ndarray:
+    """The fp32 log-probs as a 16-bit decoder would hand them over: rounded once more, to nearest
+    even, to IEEE binary16 ("f16") or bfloat16 ("bf16"); returned as the uint16 bit patterns."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if fmt == "f16":
+        with np.errstate(over="ignore"):
+            return x.astype(np.float16).view(np.uint16)
+    if fmt == "bf16":
+        u = x.view(np.uint32)
+        nan = (u & np.uint32(0x7FFFFFFF)) > np.uint32(0x7F800000)
+        r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+        r = np.where(nan, (u >> np.uint32(16)) | np.uint32(0x40), r)
+        return r.astype(np.uint16)
+    raise ValueError(f"unknown 16-bit format {fmt!r}")
+
+
 def _draw_token(rs: Stream, V: int, used: Optional[set] = None) -> int:
     while True:
         w = rs.randint(FIRST_FREE_ID, V - 1)

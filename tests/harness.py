@@ -31,10 +31,12 @@ def _first_diff(name, got, want, t, sent_ids):
 def run_parity(wl: si.Workload, T: Optional[int] = None, oracle_sentences: Optional[Sequence[int]] = None,
                check_state_every: int = 1, check_invariants: bool = True, progress: str = "",
                options: Optional[dict] = None, adjust: bool = True, normalize: bool = False,
-               prune: Optional[float] = None):
+               prune: Optional[float] = None, logp_format: Optional[str] = None):
     """Runs T steps of wl on the GPU and on the oracle (all sentences, or the sampled ones) and
     compares every step.  Returns the session's finalize() result after checking it too.
-    adjust / normalize / prune switch the same variant on both sides (Sec. 5; Sec. 4)."""
+    adjust / normalize / prune switch the same variant on both sides (Sec. 5; Sec. 4).
+    logp_format "f16" / "bf16": the generator's log-probs are rounded once more to that type; the
+    GPU gets the 16-bit tensor, the oracle the same values widened (exactly) to fp32."""
     import paper_1804_06609_amd as dba
     options = dict(options or {})
     options[dba.DBA_OPT_ADJUSTMENT] = int(adjust)
@@ -48,10 +50,16 @@ def run_parity(wl: si.Workload, T: Optional[int] = None, oracle_sentences: Optio
     ob = oracle.BatchBeam(k, V, wl.constraints, wl.eos_id, wl.pad_id, sentences=sent, adjust=adjust,
                           normalize_finished=normalize, prune_threshold=prune)
     host = torch.empty((B, k, V), dtype=torch.float32, pin_memory=True)
-    dev = torch.empty((B, k, V), dtype=torch.float32, device="cuda")
+    tdt = {None: torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[logp_format]
+    dev = torch.empty((B, k, V), dtype=tdt, device="cuda")
     for t in range(T):
         lp = wl.logp(t, out=host.numpy())
-        dev.copy_(host, non_blocking=False)
+        if logp_format is None:
+            dev.copy_(host, non_blocking=False)
+        else:
+            bits = si.narrow16(lp, logp_format)
+            dev.copy_(torch.from_numpy(bits.view(np.int16)).view(tdt))
+            lp = oracle.widen16(bits, logp_format)
         ses.step(dev)
         ob.step(lp[sent], threads=THREADS)
         g_tok, g_bp, g_sc, g_fl = ses.outputs()

@@ -187,6 +187,43 @@ def test_gbs_simulation(torch_gpu):
     _harness().run_parity(wl, adjust=False)
 
 
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
+@pytest.mark.parametrize("seed", range(8))
+def test_16bit_logp_small(torch_gpu, seed, fmt):
+    """16-bit log-probs (widened exactly, fp32 sums): odd V, so rows start at every 2-byte
+    offset inside a 16-byte group; many exact ties, because 16-bit values collide."""
+    rs = si.Stream(seed, 8)
+    B = rs.randint(2, 5)
+    k = [1, 3, 8, 13, 20, 33, 64, 5][seed % 8]
+    V = max(k + 3, [67, 131, 1001, 1023, 2051, 4099, 515, 9001][(seed // 2 + seed) % 8])
+    T = rs.randint(6, 12)
+    wl = si.make_small(9500 + seed, B, k, V, T, max_phrases=5, max_len=4, dup_prob=0.35)
+    wl.eos_switch = T // 2
+    _harness().run_parity(wl, logp_format=fmt)
+
+
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
+def test_16bit_logp_config2_paper_setup(torch_gpu, fmt):
+    wl = si.make_config(2, T=25)
+    wl.eos_switch = 10
+    _harness().run_parity(wl, logp_format=fmt, normalize=True, prune=20.0)
+
+
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
+def test_16bit_logp_config4(torch_gpu, fmt):
+    """The headline shapes with 16-bit log-probs, 12 steps, oracle on 16 sampled sentences."""
+    wl = si.make_config(4, T=12)
+    _harness().run_parity(wl, logp_format=fmt, oracle_sentences=range(0, 64, 4), check_state_every=4,
+                          progress=f"config4 {fmt}")
+
+
+def test_16bit_logp_one_launch_form(torch_gpu):
+    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
+    wl = si.make_small(9600, 3, 13, 1023, 10, max_phrases=5, max_len=4, dup_prob=0.35)
+    wl.eos_switch = 5
+    _harness().run_parity(wl, logp_format="bf16", options={DBA_OPT_FUSED_LAUNCH: 1})
+
+
 def test_call_order_errors(torch_gpu):
     """More than N steps, and an option change after the first step, are refused (no launch)."""
     import paper_1804_06609_amd as dba

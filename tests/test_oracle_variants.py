@@ -222,3 +222,54 @@ def test_a_huge_threshold_prunes_nothing_and_a_finished_beam_stays_put():
         elif c.all_finished:
             stopped_at = t
     assert stopped_at is not None and stopped_at < T - 1
+
+
+# ---- 16-bit log-probs: the exactness contract ------------------------------------------------
+def _decode16(bits: int, ebits: int, mbits: int) -> float:
+    """Value of a 16-bit binary float from its fields, in exact Python arithmetic."""
+    sign = -1.0 if bits >> 15 else 1.0
+    e = (bits >> mbits) & ((1 << ebits) - 1)
+    m = bits & ((1 << mbits) - 1)
+    bias = (1 << (ebits - 1)) - 1
+    if e == (1 << ebits) - 1:
+        return sign * float("inf") if m == 0 else float("nan")
+    if e == 0:
+        return sign * m * 2.0 ** (1 - bias - mbits)
+    return sign * (1.0 + m * 2.0 ** -mbits) * 2.0 ** (e - bias)
+
+
+@pytest.mark.parametrize("fmt,ebits,mbits", [("f16", 5, 10), ("bf16", 8, 7)])
+def test_widening_is_exact_for_every_bit_pattern(fmt, ebits, mbits):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    with np.errstate(invalid="ignore"):
+        got = oracle.widen16(bits, fmt)
+    want = np.array([_decode16(int(b), ebits, mbits) for b in bits], dtype=np.float64)
+    ok = (got.astype(np.float64) == want) | (np.isnan(got) & np.isnan(want))
+    assert ok.all()
+    assert (np.signbit(got) == (bits >> 15).astype(bool)).all()         # -0.0 stays -0.0
+
+
+@pytest.mark.parametrize("fmt,ebits,mbits", [("f16", 5, 10), ("bf16", 8, 7)])
+def test_narrowing_rounds_to_the_nearest_value_ties_to_even(fmt, ebits, mbits):
+    """The input generator's rounding: the nearest representable value, checked against all
+    neighbours on a sample that includes exact ties."""
+    with np.errstate(invalid="ignore"):
+        grid = oracle.widen16(np.arange(65536, dtype=np.uint32).astype(np.uint16), fmt).astype(np.float64)
+    finite = np.isfinite(grid)
+    vals = np.sort(np.unique(grid[finite]))
+    rs = np.random.default_rng(7)
+    x = np.concatenate([-np.exp(rs.uniform(-12, 4, 4000)), (vals[1000:1200] + vals[1001:1201]) / 2,
+                        [0.0, -0.0, -np.inf]]).astype(np.float32)
+    got = oracle.widen16(si.narrow16(x, fmt), fmt).astype(np.float64)
+    for xi, gi in zip(x.astype(np.float64), got):
+        if not np.isfinite(xi):
+            assert gi == xi
+            continue
+        j = np.searchsorted(vals, xi)
+        near = vals[max(0, j - 1):j + 2]
+        best = np.abs(near - xi).min()
+        assert abs(gi - xi) == best, (xi, gi)
+        ties = near[np.abs(near - xi) == best]
+        if len(ties) == 2:                       # exact tie: the one with an even last bit
+            b = int(si.narrow16(np.array([xi], np.float32), fmt)[0])
+            assert b & 1 == 0
