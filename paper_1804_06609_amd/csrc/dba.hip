@@ -65,6 +65,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
     st.floor = -INFINITY;
     st.thr = kLowestFinite;
     u64 ckey = 0;
+    int parked = 0;
     if (prev > -INFINITY && !(fin & kFinFinished) && !known_empty) {
         // Alg. 2 inner loop / Sec. 3.1 item 2: the hypothesis extended by each constraint token
         // it may place now; the log-prob is one 4-byte read per token, in flight during the stream
@@ -75,7 +76,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
         const float cx = cw >= 0 ? Logp<FMT>::widen_one(logp_row[cw]) : -INFINITY;
         // Sec. 3.3: no end-of-sentence before all constraints are met
         const int eos_block = (fin & kFinEosBlocked) ? p.eos_id : -1;
-        rs.run(prev, eos_block, code_base, p.k, wave, nwaves, sm, st);
+        parked = rs.run(prev, eos_block, code_base, p.k, wave, nwaves, sm, st);
         const float cs = prev + cx;
         if (cw >= 0 && cs > -INFINITY)
             ckey = pack_sel(p.met_bits, cbank, ord_from_float(cs), code_base | (uint32_t)cw);
@@ -89,13 +90,11 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
         if (PUBLISH) __hip_atomic_store(dst, ckey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else *dst = ckey;
     }
-    if (nwaves > 1) {
-        sm.wl[wave][lane] = st.list;
-        __syncthreads();
-    }
-    if (wave == 0) {
-        u64 acc = st.list;
-        for (int w = 1; w < nwaves; ++w) acc = merge_desc<u64, true>(acc, sm.wl[w][lane]);
+    // workgroups are dealt out round-robin over the 256 compute units, so the ones sharing a
+    // compute unit differ in blockIdx / 256: let that pick the wave (hence the SIMD) that finishes
+    const int fin_wave = (int)((blockIdx.x >> 8) & (unsigned)(nwaves - 1));
+    const u64 acc = finish_row(sm, st.list, parked, wave, nwaves, fin_wave);
+    if (wave == fin_wave) {
         u64 *dst = p.rowlists + (size_t)row * kWave + lane;
         if (PUBLISH) __hip_atomic_store(dst, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else *dst = acc;

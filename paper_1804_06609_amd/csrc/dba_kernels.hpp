@@ -150,18 +150,6 @@ __device__ __attribute__((noinline)) u64 fold_stage(u64 list, const u64 *stage, 
     return list;
 }
 
-// The same at the end of the row, when nothing is left to overlap with: shortest latency.
-__device__ __forceinline__ u64 fold_stage_last(u64 list, const u64 *stage, int cnt)
-{
-    const int lane = lane_id();
-    for (int base = 0; base < cnt; base += kWave) {
-        const u64 key = (base + lane < cnt) ? stage[base + lane] : 0ull;
-        const u64 sorted = sort64_desc<u64, true>(key);
-        list = (base == 0 && list == 0) ? sorted : merge_desc<u64, true>(list, sorted);
-    }
-    return list;
-}
-
 __device__ __forceinline__ void flush_stage(RowTop &st, u64 *stage, int &cnt, int kk)
 {
     st.list = fold_stage(st.list, stage, cnt);
@@ -374,6 +362,8 @@ struct StreamSmem {
     u64 stage[kWavesPerBlock][kStageCap];   // candidates parked between flushes
     uint32_t boot[kWavesPerBlock][kWave];   // sorted per-lane maxima of every wave's first tile (order images)
     unsigned int thr;                   // best bound any wave has published (order-preserving u32)
+    int parked[kWavesPerBlock];         // end of the row: keys each wave has left in its stage,
+    int has_list[kWavesPerBlock];       // and whether it holds a list from earlier folds
 };
 
 // One wave's share of one row: tiles wave, wave+nwaves, ... of 64*U groups of 16 bytes each.
@@ -424,13 +414,14 @@ struct RowStream {
         if (wave + nwaves < ntiles) load_tile<U>(vec, nv, wave + nwaves, lane, nxt, F::neg_inf());
     }
 
-    __device__ __forceinline__ void run(float prev, int eos_block, uint32_t flat_base, int kk, int wave,
-                                        int nwaves, StreamSmem &sm, RowTop &st);
+    // Returns the number of keys left parked in sm.stage[wave] (not yet folded into st.list).
+    __device__ __forceinline__ int run(float prev, int eos_block, uint32_t flat_base, int kk, int wave,
+                                       int nwaves, StreamSmem &sm, RowTop &st);
 };
 
 template <int U, int FMT>
-__device__ __forceinline__ void RowStream<U, FMT>::run(float prev, int eos_block, uint32_t flat_base, int kk,
-                                                       int wave, int nwaves, StreamSmem &sm, RowTop &st)
+__device__ __forceinline__ int RowStream<U, FMT>::run(float prev, int eos_block, uint32_t flat_base, int kk,
+                                                      int wave, int nwaves, StreamSmem &sm, RowTop &st)
 {
     const int lane = lane_id();
     constexpr int kTileElems = G * kWave * U;
@@ -527,7 +518,70 @@ __device__ __forceinline__ void RowStream<U, FMT>::run(float prev, int eos_block
             cnt += 1;
         }
     }
-    if (cnt > 0) st.list = fold_stage_last(st.list, stage, cnt);
+    return cnt;
+}
+
+// End of a row.  Each wave arrives with a sorted list from earlier folds (usually none: with
+// the floor in place a wave parks a few dozen keys per row and never fills its stage) and the
+// keys still parked in its stage.  The parked keys of all waves are pooled and sorted in chunks
+// of 64 - one chunk in the common case, sorted by one wave - instead of one sort per wave plus
+// a merge per wave.  The wave that finishes the row (fin_wave) rotates with the row index, so
+// that the rows sharing a compute unit finish on different SIMDs.  Returns the row's list to
+// the lanes of fin_wave.  Called by every thread of the workgroup (one or two barriers).
+__device__ __forceinline__ u64 finish_row(StreamSmem &sm, u64 list, int parked, int wave, int nwaves,
+                                          int fin_wave)
+{
+    const int lane = lane_id();
+    const bool mine_has = read_lane(list, 0) != 0;
+    if (lane == 0) {
+        sm.parked[wave] = parked;
+        sm.has_list[wave] = mine_has ? 1 : 0;
+    }
+    __syncthreads();
+    int n1 = sm.parked[0], n2 = n1, n3 = n1, n = n1, any = sm.has_list[0];
+    if (nwaves > 1) {
+        n2 = n1 + sm.parked[1];
+        n3 = n2;
+        n = n2;
+        any |= sm.has_list[1];
+    }
+    if (nwaves > 2) {
+        n3 = n2 + sm.parked[2];
+        n = n3 + sm.parked[3];
+        any |= sm.has_list[2] | sm.has_list[3];
+    }
+    const int nchunks = (n + kWave - 1) >> 6;
+    u64 part = 0;
+    bool have = false;
+    for (int c = (wave - fin_wave) & (nwaves - 1); c < nchunks; c += nwaves) {
+        const int i = c * kWave + lane;
+        u64 key = 0;
+        if (i < n) {
+            const int w = (i >= n1 ? 1 : 0) + (i >= n2 ? 1 : 0) + (i >= n3 ? 1 : 0);
+            const int first = w == 0 ? 0 : (w == 1 ? n1 : (w == 2 ? n2 : n3));
+            key = sm.stage[w][i - first];
+        }
+        const u64 sorted = sort64_desc<u64, true>(key);
+        part = have ? merge_desc<u64, true>(part, sorted) : sorted;
+        have = true;
+    }
+    if (nchunks <= 1 && !any) return part;            // the whole row was one chunk of fin_wave's
+    if (mine_has) {
+        part = have ? merge_desc<u64, true>(part, list) : list;
+        have = true;
+    }
+    sm.wl[wave][lane] = part;
+    __syncthreads();
+    if (wave == fin_wave) {
+        for (int w = 1; w < nwaves; ++w) {
+            const u64 other = sm.wl[(wave + w) & (nwaves - 1)][lane];
+            if (read_lane(other, 0) != 0) {
+                part = have ? merge_desc<u64, true>(part, other) : other;
+                have = true;
+            }
+        }
+    }
+    return part;
 }
 
 // ---------------------------------------------------------------------------
