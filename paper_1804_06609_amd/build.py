@@ -30,5 +30,21 @@ def build(force: bool = True, extra=()) -> str:
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(os.path.dirname(HERE), "examples", "decode_from_file.c")
+EXAMPLE_BIN = os.path.join(os.path.dirname(HERE), "examples", "decode_from_file")
+
+
+def build_example() -> str:
+    """Compiles the plain-C caller of the library with the host C compiler (no hipcc: the
+    boundary is a C ABI) and links it against libdba.so and the HIP runtime."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    subprocess.check_call([
+        "gcc", "-O1", "-Wall", "-std=c11", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include", EXAMPLE_SRC,
+        "-o", EXAMPLE_BIN, f"-L{rocm}/lib", "-lamdhip64", f"-L{HERE}", "-ldba",
+        "-Wl,-rpath,$ORIGIN/../paper_1804_06609_amd", f"-Wl,-rpath,{rocm}/lib"])
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     print(build(force=True, extra=sys.argv[1:]))
+    print(build_example())

@@ -224,6 +224,50 @@ def test_16bit_logp_one_launch_form(torch_gpu):
     _harness().run_parity(wl, logp_format="bf16", options={DBA_OPT_FUSED_LAUNCH: 1})
 
 
+@pytest.mark.parametrize("k,V", [(64, 1 << 19), (2, 1 << 24)])
+def test_widest_coordinates(torch_gpu, k, V):
+    """The limits of the key packing, bits(k-1) + bits(V-1) + bits(64) = 32: the widest beam with
+    the largest vocabulary it allows, and the largest vocabulary of all; 64 constraint tokens."""
+    B, T = 1, 3
+    cons = si.fixed_total_constraints(97, B, V, 64, max_len=4)
+    wl = si.Workload(B=B, k=k, V=V, T=T, seed=97 + k, constraints=cons,
+                     boost_tokens=[[w for p in s for w in p] for s in cons], boost_prob=0.3, boost_value=9.0)
+    _harness().run_parity(wl, progress=f"k={k} V={V}")
+
+
+def test_plain_c_caller(torch_gpu, tmp_path):
+    """examples/decode_from_file.c (built with gcc, no binding in between) against the oracle."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "examples", "decode_from_file")
+    assert os.path.exists(exe), "build it first: python -m paper_1804_06609_amd.build"
+    wl = si.make_small(4711, 3, 4, 203, 9, max_phrases=3, max_len=3)
+    wl.eos_switch = 4
+    toks, poff, soff = wl.csr()
+    lp = np.stack([wl.logp(t) for t in range(wl.T)])
+    lp.tofile(tmp_path / "logp.bin")
+    with open(tmp_path / "cons.txt", "w") as f:
+        f.write(f"{len(toks)} {len(poff) - 1}\n" + " ".join(map(str, toks)) + "\n" +
+                " ".join(map(str, poff)) + "\n" + " ".join(map(str, soff)) + "\n")
+    out = subprocess.run([exe, str(wl.B), str(wl.k), str(wl.V), str(wl.T), str(wl.eos_id), str(wl.pad_id),
+                          str(tmp_path / "logp.bin"), str(tmp_path / "cons.txt")],
+                         capture_output=True, text=True, timeout=100)
+    assert out.returncode == 0, out.stderr
+    ob = oracle.BatchBeam(wl.k, wl.V, wl.constraints, wl.eos_id, wl.pad_id)
+    want = []
+    for t in range(wl.T):
+        ob.step(lp[t])
+        for b, bm in enumerate(ob.beams):
+            cells = " ".join(f"{int(w)}/{int(h)}/{int(np.float32(s).view(np.uint32)):08x}"
+                             for w, h, s in zip(bm.token, bm.backptr, bm.score))
+            want.append(f"step {t} sent {b} : {cells}")
+    ft, fl, fs, fst = ob.finalize(wl.T)
+    for b in range(wl.B):
+        tail = "".join(f" {int(w)}" for w in ft[b][:fl[b]])
+        want.append(f"final {b} : {int(fst[b])} {int(fl[b])} {int(np.float32(fs[b]).view(np.uint32)):08x} :{tail}")
+    assert out.stdout.strip().splitlines() == want
+
+
 def test_call_order_errors(torch_gpu):
     """More than N steps, and an option change after the first step, are refused (no launch)."""
     import paper_1804_06609_amd as dba
@@ -234,6 +278,11 @@ def test_call_order_errors(torch_gpu):
     dev = torch_gpu.from_numpy(wl.logp(0)).cuda()
     with pytest.raises(dba.DbaError, match="unknown option"):
         dba.dba_set_option(ses.ctx, 9999, 1)
+    with pytest.raises(dba.DbaError, match="unknown log-prob format"):
+        dba.dba_step_fmt(ses.ctx, dev.data_ptr(), 7)
+    with pytest.raises(dba.DbaError, match="aligned"):
+        dba.dba_step(ses.ctx, dev.data_ptr() + 2)
+    assert dba.dba_steps_done(ses.ctx) == 0
     ses.step(dev)
     with pytest.raises(dba.DbaError, match="first step"):
         dba.dba_set_option(ses.ctx, dba.DBA_OPT_FUSED_LAUNCH, 1)
