@@ -235,6 +235,18 @@ def test_widest_coordinates(torch_gpu, k, V):
     _harness().run_parity(wl, progress=f"k={k} V={V}")
 
 
+@pytest.mark.parametrize("fmt", [None, "f16", "bf16"])
+@pytest.mark.parametrize("B,k,V", [(2, 3, 9001), (1, 16, 20011), (1, 8, 33333), (3, 20, 12345)])
+def test_small_batches_long_rows(torch_gpu, B, k, V, fmt):
+    """Few rows of odd length and alignment, all three element types; hypotheses finish half
+    way, so finished and empty rows take part too."""
+    T = 10
+    wl = si.make_small(9700 + k, B, k, V, T, max_phrases=5, max_len=3, dup_prob=0.3)
+    wl.eos_switch = 4
+    wl.eos_high = 1.0
+    _harness().run_parity(wl, logp_format=fmt)
+
+
 def test_plain_c_caller(torch_gpu, tmp_path):
     """examples/decode_from_file.c (built with gcc, no binding in between) against the oracle."""
     import os
