@@ -104,6 +104,7 @@ struct MergeSmem {
     int start[kMaxCons + 1];
     int ncand;
     int nsel;
+    u64 kept;                         // pruning: bit i = the hypothesis at place i of the new beam stays
 };
 
 // ---------------------------------------------------------------------------
@@ -796,6 +797,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     if (tid == 0) {
         sm.ncand = 0;
         sm.nsel = 0;
+        sm.kept = 0;
     }
     if (tid < k) {
         HypState hs;
@@ -966,12 +968,16 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     // ---- new beam, best first (Sec. 3.1); empty slots last ---------------------------------
     const int nsel = sm.nsel;
     if (wave == 0) {
-        const u64 mine = sort64_desc<u64, true>(lane < nsel ? sm.sel[lane] : 0ull);   // lane = new slot
+        // one lane per selected candidate; its place in the new beam is the number of selected
+        // keys greater than its own (at most 64 uniform LDS reads: cheaper than a 64-lane sort)
+        const bool live = lane < nsel;
+        const u64 mine = live ? sm.sel[lane] : 0ull;
+        int slot = 0;
+        for (int j = 0; j < nsel; ++j) slot += sm.sel[j] > mine ? 1 : 0;
         int token = p.pad_id, parent = -1, length = 0, ipq2 = -1, nxt2 = -1;
         float score = -INFINITY;
         u64 met2 = 0, inc2 = 0;
         uint8_t flags = 2, fin2 = 0;
-        const bool live = lane < nsel;
         if (live) {
             const uint32_t code = flatmask - ((uint32_t)mine & flatmask);
             parent = (int)(code >> p.tok_bits);
@@ -1030,14 +1036,16 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         // Sec. 4 / Sec. 6.3: hypotheses, completed or not, below (best completed - threshold) leave
         // the beam; the others close ranks
         bool keep = live;
-        int slot = lane, nlive = nsel;
+        int nlive = nsel;
         if (p.prune >= 0.0f) {
             float best = (live && fin2) ? score : -INFINITY;
 #pragma unroll
             for (int d = 32; d >= 1; d >>= 1) best = fmaxf(best, __shfl_xor(best, d, kWave));
             if (best > -INFINITY) keep = live && score >= best - p.prune;
-            const u64 km = __ballot(keep);
-            slot = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(km >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)km, 0u));
+            if (keep) atomicOr(&sm.kept, 1ull << slot);
+            // every lane's OR belongs to the one LDS instruction issued before this read
+            const u64 km = __hip_atomic_load(&sm.kept, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            slot = __popcll(km & ((1ull << slot) - 1ull));
             nlive = __popcll(km);
         }
         const u64 open = __ballot(keep && !fin2);
