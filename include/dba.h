@@ -185,10 +185,14 @@ DBA_API int dba_get_state(dba_ctx *ctx, float *score_host, uint64_t *met_mask_ho
 DBA_API int dba_set_option(dba_ctx *ctx, int option, double value);
 
 /*
- * The stopping test of Sec. 4 (synchronises the stream): all_finished_host, host [B] uint8,
- * receives 1 for every sentence whose beam is not empty and holds completed hypotheses only
- * (further steps would only carry them along), else 0.
+ * The stopping tests (synchronises the stream): all_finished_host, host [B] uint8, receives for
+ * every sentence DBA_STOP_ALL (bit 0) when its beam is not empty and holds completed hypotheses
+ * only - Sec. 4: decoding stops, further steps would only carry them along - and DBA_STOP_ANY
+ * (bit 1) when at least one hypothesis on the beam is completed - the early stopping that
+ * Sec. 6.3 mentions as the alternative to pruning.  0 before the first step.
  */
+#define DBA_STOP_ALL 1
+#define DBA_STOP_ANY 2
 DBA_API int dba_get_finished(dba_ctx *ctx, uint8_t *all_finished_host);
 
 /* Number of dba_step calls made so far (or DBA_EINVAL). */

@@ -114,6 +114,8 @@ class SentenceBeam:
         self.adjust, self.normalize_finished = bool(adjust), bool(normalize_finished)
         self.prune_threshold = -1.0 if prune_threshold is None else float(prune_threshold)
         self.all_finished = 0
+        self.any_finished = 0
+        self.stop_bits = 0
         self.phrases = [list(p) for p in phrases]
         self.off, self.tok = _phrase_arrays(self.phrases)
         self.P = len(self.phrases)
@@ -166,7 +168,9 @@ class SentenceBeam:
             _ptr(o_met), _ptr(o_ip), _ptr(o_iq), _ptr(o_len), _ptr(d_n), _ptr(d_flat),
             _ptr(d_bank), _ptr(d_cnt), _ptr(d_alloc), int(self.adjust), int(self.normalize_finished),
             self.prune_threshold, _ptr(done))
-        self.all_finished = int(done[0])
+        self.all_finished = int(done[0]) & 1          # Sec. 4: every hypothesis on the beam is completed
+        self.any_finished = (int(done[0]) >> 1) & 1   # Sec. 6.3: some hypothesis is completed
+        self.stop_bits = int(done[0])
         if rc != 0:
             raise ValueError("dba_oracle_step rejected its arguments")
         self.token, self.backptr, self.score, self.flags = o_tok, o_bp, o_sc, o_fl

@@ -166,5 +166,6 @@ def step(beam: List[Optional[Hyp]], logp: np.ndarray, phrases, eos_id: int, pad_
             cut = np.float32(max(done)) - np.float32(prune)
             out = [x for x in out if not np.float32(x[2].score) < cut]
     stop = bool(out) and all(new.finished for _, _, new in out)
+    some = any(new.finished for _, _, new in out)
     out += [None] * (k - len(out))
-    return out, dict(cands=sorted(cands), topk=topk, cnt=cnt, alloc=alloc, all_finished=stop)
+    return out, dict(cands=sorted(cands), topk=topk, cnt=cnt, alloc=alloc, all_finished=stop, any_finished=some)

@@ -268,8 +268,10 @@ static void sort_cands(cand_t **v, int n)
  *      completed or not, whose stored score is below (best stored score of a
  *      completed hypothesis on the new beam) - threshold is removed (Sec. 4);
  *      the rest close ranks in order.  No completed hypothesis: no pruning.
- *   out_all_finished    receives 1 when the new beam is not empty and all its
- *      hypotheses are completed - the stopping test of Sec. 4.
+ *   out_all_finished    receives the stopping tests as two bits: 1 when the new
+ *      beam is not empty and all its hypotheses are completed (Sec. 4), 2 when
+ *      at least one hypothesis on it is completed (the early stopping that
+ *      Sec. 6.3 mentions as the alternative to pruning).
  * Returns 0, or -1 on bad arguments.
  */
 int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *phrase_off,
@@ -466,12 +468,14 @@ int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *
             nsel = m;
         }
     }
-    /* stopping test (Sec. 4) */
+    /* stopping tests (Sec. 4; Sec. 6.3) */
     if (out_all_finished) {
-        int all = nsel > 0;
-        for (int i = 0; i < nsel; ++i)
+        int all = nsel > 0, any = 0;
+        for (int i = 0; i < nsel; ++i) {
             if (!(out_flags[i] & FLAG_FINISHED)) all = 0;
-        *out_all_finished = all;
+            else any = 1;
+        }
+        *out_all_finished = all | (any << 1);
     }
 
     if (dbg_ncand) *dbg_ncand = n;

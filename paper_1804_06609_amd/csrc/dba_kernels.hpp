@@ -74,7 +74,8 @@ struct StepParams {
     float *out_score;
     uint8_t *out_flags;
     int32_t *hist_token, *hist_backptr;   // row t of the history, [B,k]
-    uint8_t *all_finished;            // [B] 1: the new beam is not empty and every hypothesis on it is completed
+    uint8_t *all_finished;            // [B] bit 0: the new beam is not empty and every hypothesis on it is completed;
+                                      //     bit 1: some hypothesis on it is completed
 };
 
 // constraints of one sentence: token ids phrase after phrase, phrase p = tok[poff[p] .. poff[p+1])
@@ -1081,7 +1082,9 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             if (p.out_score) p.out_score[o] = -INFINITY;
             if (p.out_flags) p.out_flags[o] = 2;
         }
-        if (lane == 0) p.all_finished[b] = (uint8_t)((nlive > 0 && open == 0) ? 1 : 0);   // stopping test, Sec. 4
+        const u64 closed = __ballot(keep && fin2);
+        if (lane == 0)                                    // stopping tests: Sec. 4 (all), Sec. 6.3 (any)
+            p.all_finished[b] = (uint8_t)(((nlive > 0 && open == 0) ? 1 : 0) | (closed != 0 ? 2 : 0));
     }
 }
 

@@ -65,7 +65,7 @@ class Session:
         return st
 
     def finished(self) -> np.ndarray:
-        """[B] uint8: 1 where every hypothesis on the sentence's beam is completed (synchronises)."""
+        """[B] uint8 of DBA_STOP_ALL / DBA_STOP_ANY bits per sentence (synchronises)."""
         done = np.empty(self.B, np.uint8)
         _b.dba_get_finished(self.ctx, done)
         return done

@@ -76,7 +76,7 @@ def run_parity(wl: si.Workload, T: Optional[int] = None, oracle_sentences: Optio
             _first_diff("state.length", st["length"][sent], ob.stacked("len"), t, sent)
             _first_diff("state.flags", st["flags"][sent], ob.stacked("flags"), t, sent)
         done = ses.finished()
-        assert done[sent].tolist() == [bm.all_finished for bm in ob.beams], f"all-finished flags, step {t}"
+        assert done[sent].tolist() == [bm.stop_bits for bm in ob.beams], f"stopping flags, step {t}"
         if check_invariants:
             check_step_properties(wl, g_tok, g_bp, g_sc, g_fl, ordered=not normalize)
         if progress and (t % 10 == 9 or t == T - 1):

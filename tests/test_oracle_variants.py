@@ -79,6 +79,7 @@ def test_variants_match_brute_force(seed, vi):
         bm.step(logp, debug=True)
         assert list(bm.dbg["alloc"]) == info["alloc"]
         assert bm.all_finished == int(info["all_finished"])
+        assert bm.any_finished == int(info["any_finished"])
         for i, item in enumerate(new):
             if item is None:
                 assert bm.flags[i] == oracle.FLAG_DEAD and bm.backptr[i] == -1
@@ -244,7 +245,8 @@ def test_widening_is_exact_for_every_bit_pattern(fmt, ebits, mbits):
     with np.errstate(invalid="ignore"):
         got = oracle.widen16(bits, fmt)
     want = np.array([_decode16(int(b), ebits, mbits) for b in bits], dtype=np.float64)
-    ok = (got.astype(np.float64) == want) | (np.isnan(got) & np.isnan(want))
+    with np.errstate(invalid="ignore"):
+        ok = (got.astype(np.float64) == want) | (np.isnan(got) & np.isnan(want))
     assert ok.all()
     assert (np.signbit(got) == (bits >> 15).astype(bool)).all()         # -0.0 stays -0.0
 
