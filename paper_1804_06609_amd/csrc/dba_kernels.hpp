@@ -704,17 +704,6 @@ __device__ __forceinline__ u64 body_from_rowkey(int met_bits, u64 key)
     return pack_sel(met_bits, 0, (uint32_t)(key >> 32), key_flat(key));
 }
 
-// number of keys greater than x in a[0..64), a sorted in decreasing order
-__device__ __forceinline__ int count_greater64(const u64 *a, u64 x)
-{
-    if (a[63] > x) return 64;
-    int pos = 0;
-#pragma unroll
-    for (int step = 32; step >= 1; step >>= 1)
-        if (a[pos + step - 1] > x) pos += step;
-    return pos;
-}
-
 // Wave-wide: lane i holds token w (or -1).  Returns to lane i the set of phrases whose first
 // token is w, as a bit mask; ftok = this lane's phrase's first token (lane < P).  bloom has
 // bit (t & 63) set for every first token t, so most lanes are settled without a look.

@@ -43,7 +43,6 @@ __device__ __forceinline__ u64 make_key(float s, uint32_t flat)
 }
 
 __device__ __forceinline__ uint32_t key_flat(u64 key) { return 0xFFFFFFFFu - (uint32_t)key; }
-__device__ __forceinline__ float key_score(u64 key) { return float_from_ord((uint32_t)(key >> 32)); }
 
 // Wave-uniform read of one lane's key (lane index must be wave-uniform).
 __device__ __forceinline__ u64 read_lane(u64 v, int l)
@@ -52,9 +51,6 @@ __device__ __forceinline__ u64 read_lane(u64 v, int l)
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l);
     return ((u64)hi << 32) | lo;
 }
-
-__device__ __forceinline__ u64 umax64(u64 a, u64 b) { return a > b ? a : b; }
-__device__ __forceinline__ u64 umin64(u64 a, u64 b) { return a < b ? a : b; }
 
 // ---- lane permutations of one 32-bit register ------------------------------
 constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
