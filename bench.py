@@ -15,7 +15,7 @@ Prints ONE JSON line.  `value` = steps/s (wall clock, synchronised on both sides
 (dba_stream_kernel, which reads the log-probs, followed by dba_merge_kernel), measured with HIP
 events on the launch stream over the timed region - the two kernels run back to back with no
 gap, so this is the sum of their durations; profiles/ holds the rocprofv3 split of the two.
-`cpu_baseline` = the CPU oracle timed on this machine's cores.
+`cpu_baseline` = the CPU oracle timed on the host's cores.
 """
 from __future__ import annotations
 
@@ -218,7 +218,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         threads = min(16, os.cpu_count() or 1)
-        S = 12 if args.config == 4 else 4
+        S = 40 if args.config == 4 else 4      # about 16 core-seconds of oracle work at config 4
         ob = oracle.BatchBeam(k, V, wl.constraints, wl.eos_id, wl.pad_id)
         ses = Session(B, k, V, S, wl.eos_id, wl.pad_id, toks, poff, soff)
         if esize == 2:
