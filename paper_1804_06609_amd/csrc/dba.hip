@@ -403,13 +403,16 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     // constraints -> fixed-stride per-sentence tables
     if (sent_offsets[0] != 0 || phrase_offsets[0] != 0)
         return fail(nullptr, DBA_EINVAL, "dba_init: offsets must start at 0");
+    // sent_offsets[B] is the length of phrase_offsets minus one: nothing beyond it is read
+    for (int b = 0; b < B; ++b)
+        if (sent_offsets[b + 1] < sent_offsets[b])
+            return fail(nullptr, DBA_EINVAL, "dba_init: sent_offsets decreases at %d", b);
     std::vector<int32_t> tok((size_t)B * kMaxCons, 0), off((size_t)B * (kMaxCons + 1), 0), nph(B, 0);
     std::vector<u64> sfl((size_t)B * kMaxCons, 0), bloom(B, 0);
     std::vector<int32_t> ftok((size_t)B * kMaxCons, -1);
     int max_tokens = 0, max_phrases = 0;
     for (int b = 0; b < B; ++b) {
         const int p0 = sent_offsets[b], p1 = sent_offsets[b + 1];
-        if (p1 < p0) return fail(nullptr, DBA_EINVAL, "dba_init: sent_offsets decreases at %d", b);
         const int t0 = phrase_offsets[p0];
         int n = 0;
         for (int p = p0; p < p1; ++p) {
