@@ -478,9 +478,10 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->adjust = 1;
     c->normalize = 0;
     c->prune = -1.0f;
-    int npad = kWave;
-    while (npad < k * (max_phrases + 2)) npad <<= 1;
-    c->dyn_smem = (size_t)npad * sizeof(u64);
+    // candidates of one sentence: at most k best + k row bests + k * phrases constraint tokens,
+    // in whole chunks of 64 keys (at most 4224 keys = 33 KB of LDS)
+    const int ncand_max = (k * (max_phrases + 2) + kWave - 1) / kWave * kWave;
+    c->dyn_smem = (size_t)ncand_max * sizeof(u64);
 
     hipError_t e;
     e = hipMemcpyAsync(at<int32_t>(c, L.cons_tok), tok.data(), tok.size() * 4, hipMemcpyHostToDevice, c->stream);

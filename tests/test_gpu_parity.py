@@ -119,6 +119,16 @@ def test_many_constraints_small_beam(torch_gpu):
     _harness().run_parity(wl)
 
 
+def test_most_candidates(torch_gpu):
+    """The widest beam with 64 one-token constraints: k * (64 + 2) candidates per sentence at most,
+    the largest candidate buffer the merge phase can need."""
+    B, k, V, T = 2, 64, 5000, 5
+    cons = si.fixed_total_constraints(61, B, V, 64, max_len=1)
+    wl = si.Workload(B=B, k=k, V=V, T=T, seed=61, constraints=cons,
+                     boost_tokens=[[w for p in s for w in p] for s in cons], boost_prob=0.5, boost_value=6.0)
+    _harness().run_parity(wl)
+
+
 def test_batch_equals_single_sentences(torch_gpu):
     """Sentences never interact: a batch run equals one-sentence runs of the same rows."""
     h = _harness()
