@@ -52,7 +52,6 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
     RowStream<U, FMT> rs;
     const bool known_empty = p.first_step && h != 0;   // decoder-init leaves slots 1.. empty
     if (!known_empty) rs.begin(logp_row, p.V, wave, nwaves);
-    if (threadIdx.x == 0) sm.thr = ord_from_float(-INFINITY);
 
     // the row's hypothesis: wave-uniform by construction, made so for the compiler
     const float prev = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(prev_ld)));

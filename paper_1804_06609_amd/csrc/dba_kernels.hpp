@@ -363,7 +363,6 @@ struct StreamSmem {
     u64 wl[kWavesPerBlock][kWave];      // the waves' lists, for the final merge
     u64 stage[kWavesPerBlock][kStageCap];   // candidates parked between flushes
     uint32_t boot[kWavesPerBlock][kWave];   // sorted per-lane maxima of every wave's first tile (order images)
-    unsigned int thr;                   // best bound any wave has published (order-preserving u32)
     int parked[kWavesPerBlock];         // end of the row: keys each wave has left in its stage,
     int has_list[kWavesPerBlock];       // and whether it holds a list from earlier folds
 };
@@ -379,11 +378,10 @@ struct StreamSmem {
 // Thresholds.  (1) Every lane takes an element of its share of the wave's first two tiles (the
 // greatest, where the format finds it cheaply); the k-th greatest of all the workgroup's
 // per-lane values is a floor: k different lanes hold an element at least that large, so nothing
-// below it can be among the row's k best.  (2) A wave whose own list holds k entries uses the
-// score of its k-th, publishes it into sm.thr (atomic max on an order-preserving u32) and
-// re-reads the workgroup's maximum once per tile.  Any wave's bound holds for the whole row, so
-// a stale value only lets a few more elements through; it never drops one.  The row's best
-// element is never below any bound, so it always survives.
+// below it can be among the row's k best.  (2) A wave whose stage fills up folds it into its
+// list; from then on the score of the list's k-th entry bounds its share of the row.  With the
+// floor in place that is rare: a wave parks about k keys per row.  The row's best element is
+// never below any bound, so it always survives.
 template <int U, int FMT>
 struct RowStream {
     typedef Logp<FMT> F;
@@ -481,16 +479,12 @@ __device__ __forceinline__ int RowStream<U, FMT>::run(float prev, int eos_block,
         }
     };
     // after a tile: start the load that refills its registers (two tiles ahead) and make the
-    // other buffer ready (end-of-sentence mask, freshest shared bound)
+    // other buffer ready (end-of-sentence mask, the quick test's form of the threshold)
     auto advance = [&](vec_t (&done)[U], vec_t (&next)[U], int next_tile) {
         if (next_tile + nwaves < ntiles) load_tile<U>(vec, nv, next_tile + nwaves, lane, done, F::neg_inf());
         if (next_tile < ntiles) {
             const int rel = eos_rel0 - next_tile * kTileElems;
             if (eos_rel0 >= 0 && rel >= 0 && rel < kTileElems) block_eos<U, FMT>(next, rel, lane);
-            if (nwaves > 1) {
-                st.floor = fmaxf(st.floor, float_from_ord(sm.thr));
-                st.thr = fmaxf(st.thr, st.floor);
-            }
             quick = F::quick(prev, st.thr);
         }
     };
