@@ -119,6 +119,15 @@ def test_many_constraints_small_beam(torch_gpu):
     _harness().run_parity(wl)
 
 
+def test_many_sentences_long_decode(torch_gpu):
+    """300 sentences (more workgroups in the merge phase than compute units), 150 steps of history,
+    the set-up of Sec. 4 (per-word scores, pruning at 20), end-of-sentence likely from step 40 on."""
+    wl = si.make_small(4242, 300, 7, 257, 150, max_phrases=4, max_len=3, dup_prob=0.3)
+    wl.eos_switch = 40
+    wl.eos_high = -2.0
+    _harness().run_parity(wl, check_state_every=10, normalize=True, prune=20.0)
+
+
 def test_most_candidates(torch_gpu):
     """The widest beam with 64 one-token constraints: k * (64 + 2) candidates per sentence at most,
     the largest candidate buffer the merge phase can need."""
