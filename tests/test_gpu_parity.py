@@ -119,6 +119,31 @@ def test_many_constraints_small_beam(torch_gpu):
     _harness().run_parity(wl)
 
 
+class _TieHeavy(si.Workload):
+    """Log-probs on a few levels only: almost every element ties with thousands of others, so the
+    order is decided by coordinates everywhere and far more elements than usual reach the
+    thresholds (the stages of the stream phase fill up and are folded many times per row)."""
+
+    levels = 3
+
+    def logp(self, t, sentences=None, out=None):
+        lp = super().logp(t, sentences, out)
+        q = np.round(lp * (self.levels / 8.0)) * (8.0 / self.levels)
+        q[..., self.eos_id] = lp[..., self.eos_id]
+        lp[...] = q.astype(np.float32)
+        return lp
+
+
+@pytest.mark.parametrize("levels,fmt", [(3, None), (1, None), (6, "bf16"), (2, "f16")])
+def test_ties_everywhere(torch_gpu, levels, fmt):
+    base = si.make_small(5151 + levels, 3, 12, 6007, 9, max_phrases=4, max_len=3, dup_prob=0.3)
+    wl = _TieHeavy(B=base.B, k=base.k, V=base.V, T=base.T, seed=base.seed, constraints=base.constraints,
+                   boost_tokens=base.boost_tokens, boost_value=4.0, boost_prob=0.35)
+    wl.levels = levels
+    wl.eos_switch = 5
+    _harness().run_parity(wl, logp_format=fmt)
+
+
 def test_many_sentences_long_decode(torch_gpu):
     """300 sentences (more workgroups in the merge phase than compute units), 150 steps of history,
     the set-up of Sec. 4 (per-word scores, pruning at 20), end-of-sentence likely from step 40 on."""
