@@ -144,6 +144,39 @@ def test_ties_everywhere(torch_gpu, levels, fmt):
     _harness().run_parity(wl, logp_format=fmt)
 
 
+class _Masked(si.Workload):
+    """A decoder with a restricted vocabulary: all but a few entries of every row are -inf (a
+    different few in every row and step), so a sentence can have fewer than k finite sums, beams
+    run partly empty, and constraint tokens are often impossible."""
+
+    keep = 6
+
+    def logp(self, t, sentences=None, out=None):
+        lp = super().logp(t, sentences, out)
+        n = lp.shape[0] * lp.shape[1]
+        flat = lp.reshape(n, self.V)
+        for r in range(n):
+            rs = si.Stream(self.seed + 977 * t, r)
+            allowed = {rs.randint(0, self.V - 1) for _ in range(rs.randint(1, self.keep))}
+            allowed.add(self.eos_id if rs.randint(0, 2) == 0 else rs.randint(4, self.V - 1))
+            if rs.randint(0, 1):
+                allowed.update(w for p in self.constraints[(r // self.k) % len(self.constraints)] for w in p[:1])
+            mask = np.ones(self.V, bool)
+            mask[list(allowed)] = False
+            flat[r, mask] = -np.inf
+        return lp
+
+
+@pytest.mark.parametrize("keep,fmt", [(2, None), (6, None), (12, "bf16"), (4, "f16")])
+def test_restricted_vocabulary(torch_gpu, keep, fmt):
+    base = si.make_small(6161 + keep, 4, 9, 1501, 10, max_phrases=3, max_len=2, dup_prob=0.2)
+    wl = _Masked(B=base.B, k=base.k, V=base.V, T=base.T, seed=base.seed, constraints=base.constraints,
+                 boost_tokens=base.boost_tokens, boost_value=4.0, boost_prob=0.35)
+    wl.keep = keep
+    wl.eos_switch = 4
+    _harness().run_parity(wl, logp_format=fmt)
+
+
 def test_many_sentences_long_decode(torch_gpu):
     """300 sentences (more workgroups in the merge phase than compute units), 150 steps of history,
     the set-up of Sec. 4 (per-word scores, pruning at 20), end-of-sentence likely from step 40 on."""
