@@ -119,6 +119,21 @@ def test_many_constraints_small_beam(torch_gpu):
     _harness().run_parity(wl)
 
 
+def test_tiny_shapes(torch_gpu):
+    """The smallest shapes: V from 5 up (ids 0..3 are reserved by the generator), k from 1 to V, one
+    and three steps, with and without constraints."""
+    h = _harness()
+    n = 0
+    for V in (5, 6, 7, 9, 16):
+        for k in sorted({1, 2, V // 2, V - 1, V}):
+            for T in (1, 3):
+                wl = si.make_small(7000 + 31 * V + k, 2, k, V, T, max_phrases=2, max_len=2, dup_prob=0.5)
+                wl.eos_switch = 1
+                h.run_parity(wl)
+                n += 1
+    assert n >= 40
+
+
 class _TieHeavy(si.Workload):
     """Log-probs on a few levels only: almost every element ties with thousands of others, so the
     order is decided by coordinates everywhere and far more elements than usual reach the
