@@ -95,16 +95,18 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
  *   logp_dev        device [B,k,V] fp32, row-major, 4-byte aligned, read only; row h of
  *                   sentence b holds the log-probabilities of extending the hypothesis in
  *                   beam slot h of the previous step's output (the "scores" matrix of
- *                   Sec. 2 before the hypothesis score is added).  Must stay valid until
- *                   the stream has passed this step.
+ *                   Sec. 2 before the hypothesis score is added).  An entry of -inf is legal
+ *                   (that extension does not exist); NaN and +inf are not.  Rows of empty
+ *                   slots are not read.  Must stay valid until the stream has passed this step.
  *   out_token_dev   device [B,k] int32: token of each new beam slot, best first (pad_id if empty)
  *   out_backptr_dev device [B,k] int32: beam slot of the parent hypothesis (-1 if empty)
  *   out_score_dev   device [B,k] fp32 : cumulative score = parent score + logp, one fp32 add
  *                   (-inf if empty)
  *   out_flags_dev   device [B,k] uint8: DBA_FLAG_* bits; may be NULL
  *
- * Any of the first three outputs may also be NULL (the beam is kept inside the
- * ctx anyway).  Asynchronous.  Errors: DBA_EINVAL (NULL ctx / logp), DBA_ESTATE
+ * Under DBA_OPT_NORMALIZE_FINISHED / DBA_OPT_PRUNE_THRESHOLD the scores and the occupied slots
+ * are as described at dba_set_option.  Any of the first three outputs may also be NULL (the beam
+ * is kept inside the ctx anyway).  Asynchronous.  Errors: DBA_EINVAL (NULL ctx / logp), DBA_ESTATE
  * after N steps, DBA_EHIP if the launch fails.
  */
 DBA_API int dba_step(dba_ctx *ctx, const float *logp_dev, int32_t *out_token_dev,
