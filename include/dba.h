@@ -96,8 +96,9 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
  *                   sentence b holds the log-probabilities of extending the hypothesis in
  *                   beam slot h of the previous step's output (the "scores" matrix of
  *                   Sec. 2 before the hypothesis score is added).  An entry of -inf is legal
- *                   (that extension does not exist); NaN and +inf are not.  Rows of empty
- *                   slots are not read.  Must stay valid until the stream has passed this step.
+ *                   (that extension does not exist); NaN and +inf are not.  The content of
+ *                   rows of empty slots is ignored, but the whole [B,k,V] extent must be
+ *                   readable.  Must stay valid until the stream has passed this step.
  *   out_token_dev   device [B,k] int32: token of each new beam slot, best first (pad_id if empty)
  *   out_backptr_dev device [B,k] int32: beam slot of the parent hypothesis (-1 if empty)
  *   out_score_dev   device [B,k] fp32 : cumulative score = parent score + logp, one fp32 add
