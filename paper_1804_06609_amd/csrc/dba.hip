@@ -305,7 +305,7 @@ Layout make_layout(size_t B, size_t k, size_t N)
     L.nphr = take(B * sizeof(int32_t));
     L.ftok = take(B * kMaxCons * sizeof(int32_t));
     L.sfl = take(B * kMaxCons * sizeof(u64));
-    L.bloom = take(B * sizeof(u64));
+    L.bloom = take(B * kMaxCons * sizeof(u64));
     L.rowlists = take(B * k * kWave * sizeof(u64));
     L.conskeys = take(B * k * kMaxCons * sizeof(u64));
     L.counters = take(B * sizeof(unsigned int));
@@ -407,7 +407,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         if (sent_offsets[b + 1] < sent_offsets[b])
             return fail(nullptr, DBA_EINVAL, "dba_init: sent_offsets decreases at %d", b);
     std::vector<int32_t> tok((size_t)B * kMaxCons, 0), off((size_t)B * (kMaxCons + 1), 0), nph(B, 0);
-    std::vector<u64> sfl((size_t)B * kMaxCons, 0), bloom(B, 0);
+    std::vector<u64> sfl((size_t)B * kMaxCons, 0), bloom((size_t)B * kMaxCons, 0);
     std::vector<int32_t> ftok((size_t)B * kMaxCons, -1);
     int max_tokens = 0, max_phrases = 0;
     for (int b = 0; b < B; ++b) {
@@ -436,11 +436,11 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         off[(size_t)b * (kMaxCons + 1) + (p1 - p0)] = n;
         nph[b] = p1 - p0;
         // lookup aids for the kernels (layout only): which lower phrases share a phrase's first
-        // token, and a 64-bit filter over the first tokens
+        // token, and the phrases bucketed by the low six bits of their first token
         for (int j = 0; j < p1 - p0; ++j) {
             const int fj = tok[(size_t)b * kMaxCons + off[(size_t)b * (kMaxCons + 1) + j]];
             ftok[(size_t)b * kMaxCons + j] = fj;
-            bloom[b] |= 1ull << (fj & 63);
+            bloom[(size_t)b * kMaxCons + (fj & 63)] |= 1ull << j;
             for (int j2 = 0; j2 < j; ++j2)
                 if (tok[(size_t)b * kMaxCons + off[(size_t)b * (kMaxCons + 1) + j2]] == fj)
                     sfl[(size_t)b * kMaxCons + j] |= 1ull << j2;
@@ -562,7 +562,7 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
     p.nphr = at<int32_t>(c, L.nphr);
     p.first_tok = at<int32_t>(c, L.ftok);
     p.same_first_lower = at<u64>(c, L.sfl);
-    p.first_bloom = at<u64>(c, L.bloom);
+    p.first_bucket = at<u64>(c, L.bloom);
     p.rowlists = at<u64>(c, L.rowlists);
     p.conskeys = at<u64>(c, L.conskeys);
     p.counters = at<unsigned int>(c, L.counters);

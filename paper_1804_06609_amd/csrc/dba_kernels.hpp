@@ -63,7 +63,7 @@ struct StepParams {
     const int32_t *nphr;              // [B]
     const int32_t *first_tok;         // [B,64] first token of phrase j
     const u64 *same_first_lower;      // [B,64] phrase j: the lower phrases with the same first token
-    const u64 *first_bloom;           // [B] bit (w & 63) set for every phrase's first token w
+    const u64 *first_bucket;          // [B,64] bucket w & 63: the phrases whose first token has these low six bits
     // scratch
     u64 *rowlists;                    // [B*k,64] sorted top keys of every row (score image, ~flat)
     u64 *conskeys;                    // [B*k,64] selection keys (bank, score image, ~flat) of the
@@ -100,6 +100,7 @@ struct MergeSmem {
     u64 rb[kMaxBeam];                 // every row's best, as a selection-key body
     u64 sel[kMaxBeam];
     ConsTab ct;
+    u64 fbucket[kMaxCons];            // phrases by the low six bits of their first token
     int cnt[kMaxCons + 1];
     int alloc[kMaxCons + 1];
     int start[kMaxCons + 1];
@@ -698,20 +699,19 @@ __device__ __forceinline__ u64 body_from_rowkey(int met_bits, u64 key)
     return pack_sel(met_bits, 0, (uint32_t)(key >> 32), key_flat(key));
 }
 
-// Wave-wide: lane i holds token w (or -1).  Returns to lane i the set of phrases whose first
-// token is w, as a bit mask; ftok = this lane's phrase's first token (lane < P).  bloom has
-// bit (t & 63) set for every first token t, so most lanes are settled without a look.
-__device__ __forceinline__ u64 first_token_matches(int w, int ftok, int P, u64 bloom)
+// The phrases whose first token is w (w < 0: none), as a bit mask.  Every lane looks its own
+// token up: the bucket of the token's low six bits names the few phrases to compare with
+// (usually none or one).
+__device__ __forceinline__ u64 first_token_matches(int w, const MergeSmem &sm)
 {
-    const int lane = lane_id();
-    u64 todo = __ballot(w >= 0 && ((bloom >> (w & 63)) & 1ull));
     u64 mine = 0;
-    while (todo) {
-        const int i = __ffsll((long long)todo) - 1;
-        todo &= todo - 1;
-        const int wi = __builtin_amdgcn_readlane(w, i);
-        const u64 mm = __ballot(lane < P && ftok == wi);
-        if (lane == i) mine = mm;
+    if (w >= 0) {
+        u64 todo = sm.fbucket[w & 63];
+        while (todo) {
+            const int j = __ffsll((long long)todo) - 1;
+            todo &= todo - 1;
+            if (sm.ct.tok[sm.ct.poff[j]] == w) mine |= 1ull << j;
+        }
     }
     return mine;
 }
@@ -746,9 +746,8 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const size_t rs = (size_t)b * k + hs;
     const int ld_poff = p.phr_off[(size_t)b * (kMaxCons + 1) + t64];
     const int ld_tok = p.cons_tok[(size_t)b * kMaxCons + lane];
-    const int ftok = p.first_tok[(size_t)b * kMaxCons + lane];   // first token of this lane's phrase, -1 beyond P
     const int P = p.nphr[b];
-    const u64 bloom = p.first_bloom[b];
+    const u64 ld_bucket = p.first_bucket[(size_t)b * kMaxCons + lane];
     const u64 ld_met = p.met_cur[rs];
     const u64 ld_inc = p.inc_cur[rs];
     const int ld_ipq = p.ipq_cur[rs];
@@ -777,7 +776,10 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         sm.ct.poff[tid] = ld_poff;
         sm.cnt[tid] = 0;
     }
-    if (tid < kMaxCons) sm.ct.tok[tid] = ld_tok;
+    if (tid < kMaxCons) {
+        sm.ct.tok[tid] = ld_tok;
+        sm.fbucket[tid] = ld_bucket;
+    }
     if (tid == 0) {
         sm.ncand = 0;
         sm.nsel = 0;
@@ -838,7 +840,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             w = (int)(code & tokmask);
         }
         const HypState hs = sm.hyp[h];
-        const u64 match = first_token_matches(w, ftok, P, bloom);
+        const u64 match = first_token_matches(w, sm);
         if (g_valid) {
             g_bank = hs.misc >> 8;
             if (!(hs.misc & kFinFinished))
@@ -968,7 +970,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             token = (int)(code & tokmask);
             score = float_from_ord((uint32_t)(mine >> fb));
         }
-        const u64 match = first_token_matches(live ? token : -1, ftok, P, bloom);
+        const u64 match = first_token_matches(live ? token : -1, sm);
         if (live) {
             const HypState hs = sm.hyp[parent];
             met2 = hs.met;
