@@ -15,6 +15,8 @@ Prints ONE JSON line.  `value` = steps/s (wall clock, synchronised on both sides
 (dba_stream_kernel, which reads the log-probs, followed by dba_merge_kernel), measured with HIP
 events on the launch stream over the timed region - the two kernels run back to back with no
 gap, so this is the sum of their durations; profiles/ holds the rocprofv3 split of the two.
+`reference_read` = a kernel of the library that only reads the same tensors once (row maxima),
+timed the same way: what the device delivers for this access pattern with no selection work.
 `cpu_baseline` = the CPU oracle timed on the host's cores.
 """
 from __future__ import annotations
@@ -207,6 +209,31 @@ def main():
             "algorithmic_bytes_per_launch": bytes_total / launches,
         },
     }
+
+    # the reference read: the same tensors, the same loads, no selection work (f32 tensors only)
+    if esize == 4:
+        from paper_1804_06609_amd import dba_debug_row_max
+        sink = torch.empty(B * k, dtype=torch.float32, device="cuda")
+        stream = torch.cuda.current_stream()
+        reps = 200
+        for i in range(20):
+            dba_debug_row_max(dev[i % R].data_ptr(), B * k, V, sink.data_ptr(), stream.cuda_stream)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for i in range(reps):
+            dba_debug_row_max(dev[i % R].data_ptr(), B * k, V, sink.data_ptr(), stream.cuda_stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        read_us = e0.elapsed_time(e1) * 1e3 / reps
+        full_step_us = ev_ms * 1e3 / launches * (4.0 * B * k * V) / (bytes_total / launches)
+        out["reference_read"] = {
+            "kernel": "dba_row_max_kernel (reads each [B,k,V] tensor once with the stream phase's loads)",
+            "us_per_launch": read_us,
+            "GBps": 4.0 * B * k * V / read_us / 1e3,
+            "step_over_read": full_step_us / read_us,
+        }
 
     if args.copy_probe:
         dst = torch.empty_like(dev[0])

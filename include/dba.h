@@ -233,6 +233,18 @@ DBA_API int dba_debug_wave_select(int n_cases, const uint64_t *keys_host, const 
                                   uint64_t *out_host, float *fout_host, void *scratch_dev,
                                   size_t scratch_bytes, void *hip_stream);
 
+/*
+ * Diagnostic: the reference read.  out_max_dev[r] = largest of the V floats of row r of
+ * src_dev [rows, V] (device, 16-byte aligned, V a multiple of 4), one workgroup per row,
+ * with the loads and the tile order of the step's streaming phase and no other work.  The
+ * step of Alg. 2 has to read its [B,k,V] scores once (Sec. 3.1: the k x V matrix is the
+ * input); this kernel's duration is what the device needs for that read alone, so a
+ * benchmark can state the step's time as a multiple of it.  Asynchronous on hip_stream;
+ * out_max_dev is device memory of `rows` floats owned by the caller.
+ */
+DBA_API int dba_debug_row_max(const float *src_dev, int rows, int V, float *out_max_dev,
+                              void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -39,6 +39,7 @@ _SIGNATURES = {
     "dba_last_error": (ctypes.c_char_p, [_P]),
     "dba_debug_allocate": (_I, [_I, _I] + [_P] * 5 + [ctypes.c_size_t, _P]),
     "dba_debug_wave_select": (_I, [_I] + [_P] * 5 + [ctypes.c_size_t, _P]),
+    "dba_debug_row_max": (_I, [_P, _I, _I, _P, _P]),
 }
 
 _lib = None
@@ -160,3 +161,7 @@ def dba_debug_wave_select(keys: np.ndarray, vals: np.ndarray, out: np.ndarray, f
     return _check(load().dba_debug_wave_select(n, _host(keys, np.uint64), _host(vals, np.float32),
                                                _host(out, np.uint64), _host(fout, np.float32),
                                                scratch_dev, scratch_bytes, hip_stream or None))
+
+
+def dba_debug_row_max(src_dev: int, rows: int, V: int, out_max_dev: int, hip_stream: int = 0) -> int:
+    return _check(load().dba_debug_row_max(src_dev, rows, V, out_max_dev, hip_stream or None))

@@ -150,6 +150,55 @@ __global__ __launch_bounds__(kBlock) void dba_merge_kernel(const StepParams p)
     merge_phase<false>(p, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
 }
 
+// Reference read: the largest element of each row, one workgroup per row, with the tile order and
+// the two-tiles-in-flight non-temporal 128-bit loads of the stream phase and nothing else.  Its
+// duration is what this chip takes to deliver the [rows, V] tensor once; the step is compared
+// with it.
+__global__ __launch_bounds__(kBlock) void dba_row_max_kernel(const float *__restrict__ src, int V,
+                                                             float *__restrict__ out)
+{
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    constexpr int U = 4;
+    __shared__ float part[kWavesPerBlock];
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const v4f *vec = reinterpret_cast<const v4f *>(src + (size_t)blockIdx.x * V);
+    const int nv = V >> 2, per = kWave * U, ntiles = (nv + per - 1) / per;
+    const float ninf = -__builtin_inff();
+    v4f a[U], b[U];
+    auto load = [&](v4f(&x)[U], int tl) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = tl * per + u * kWave + lane;
+            x[u] = i < nv ? __builtin_nontemporal_load(vec + i) : v4f{ninf, ninf, ninf, ninf};
+        }
+    };
+    float m = ninf;
+    auto fold = [&](v4f(&x)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) m = fmaxf(m, fmaxf(fmaxf(x[u].x, x[u].y), fmaxf(x[u].z, x[u].w)));
+    };
+    int tl = wave;
+    if (tl < ntiles) load(a, tl);
+    if (tl + kWavesPerBlock < ntiles) load(b, tl + kWavesPerBlock);
+    while (tl < ntiles) {
+        fold(a);
+        if (tl + 2 * kWavesPerBlock < ntiles) load(a, tl + 2 * kWavesPerBlock);
+        tl += kWavesPerBlock;
+        if (tl >= ntiles) break;
+        fold(b);
+        if (tl + 2 * kWavesPerBlock < ntiles) load(b, tl + 2 * kWavesPerBlock);
+        tl += kWavesPerBlock;
+    }
+    for (int d = 32; d > 0; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, kWave));
+    if (lane == 0) part[wave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kWavesPerBlock; ++w) m = fmaxf(m, part[w]);
+        out[blockIdx.x] = m;
+    }
+}
+
+
 // Diagnostic: the wavefront selection primitives on caller-provided keys, one wave per case.
 // in: keys[128] per case, vals[64] per case.  out[0:64] = sort of keys[0:64];
 // out[64:128] = merge of sort(keys[0:64]) and sort(keys[64:128]); out[128:192] = the first
@@ -741,6 +790,19 @@ DBA_API int dba_debug_wave_select(int n_cases, const uint64_t *keys_host, const 
     if (e == hipSuccess) e = hipMemcpyAsync(fout_host, d_fout, n * 64 * 4, hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return fail(nullptr, DBA_EHIP, "dba_debug_wave_select: HIP error: %s", hipGetErrorString(e));
+    return DBA_OK;
+}
+
+DBA_API int dba_debug_row_max(const float *src_dev, int rows, int V, float *out_max_dev, void *hip_stream)
+{
+    if (!src_dev || !out_max_dev || rows < 1 || V < 4 || (V & 3))
+        return fail(nullptr, DBA_EINVAL, "dba_debug_row_max: bad argument (V must be a multiple of 4)");
+    if (reinterpret_cast<uintptr_t>(src_dev) & 15)
+        return fail(nullptr, DBA_EINVAL, "dba_debug_row_max: src_dev must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    dba_row_max_kernel<<<dim3((unsigned)rows), dim3(kBlock), 0, s>>>(src_dev, V, out_max_dev);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(nullptr, DBA_EHIP, "dba_debug_row_max: HIP error: %s", hipGetErrorString(e));
     return DBA_OK;
 }
 

@@ -426,3 +426,24 @@ def test_config5(torch_gpu):
     ntok = [wl.n_tokens(b) for b in range(wl.B)]
     sample = sorted({int(np.argmin(ntok)), int(np.argmax(ntok)), 0, 1, 63, 64, 126, 127})
     _harness().run_parity(wl, oracle_sentences=sample, check_state_every=5, progress="config5")
+
+
+@pytest.mark.gpu
+def test_reference_read_is_the_row_maximum():
+    """The diagnostic read kernel (what the benchmark compares the step with) returns each row's
+    largest element: a ragged last tile, several tiles per wave, -inf entries and a whole row of them."""
+    import torch
+    import paper_1804_06609_amd as dba
+    rng = np.random.default_rng(77)
+    for rows, V in ((3, 4), (5, 1000), (7, 32000), (4, 50000), (2, 1028)):
+        x = rng.standard_normal((rows, V)).astype(np.float32)
+        x[0, ::3] = -np.inf
+        if rows > 2:
+            x[2, :] = -np.inf
+        d = torch.from_numpy(x).cuda()
+        out = torch.full((rows,), 123.0, dtype=torch.float32, device="cuda")
+        dba.dba_debug_row_max(d.data_ptr(), rows, V, out.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert out.cpu().numpy().tobytes() == x.max(axis=1).tobytes(), (rows, V)
+    with pytest.raises(dba.DbaError):
+        dba.dba_debug_row_max(d.data_ptr(), 2, 1027, out.data_ptr(), 0)
