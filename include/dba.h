@@ -225,9 +225,11 @@ DBA_API int dba_debug_allocate(int n_cases, int adjust, const int32_t *k_host, c
  * (64-lane sort, merge of two sorted lists, single insert) on caller data, one
  * wavefront per case, so that they can be checked against a host sort.
  *   keys_host [n_cases][128] distinct non-zero 64-bit keys, vals_host [n_cases][64] floats,
- *   out_host [n_cases][192]: sorted keys[0:64] | top 64 of all 128, sorted | sorted keys[0:64]
- *   after inserting keys[64..71]; fout_host [n_cases][64]: vals sorted.  All decreasing.
- * Host pointers; staged through scratch_dev (device, >= n_cases*3072 bytes); synchronises.
+ *   out_host [n_cases][256]: sorted keys[0:64] | top 64 of all 128, sorted | sorted keys[0:64]
+ *   after inserting keys[64..71] | low word: the 64 greatest of the 128 high words (merged as
+ *   32-bit keys, equal ones allowed), high word: the greatest high word that was left out;
+ *   fout_host [n_cases][64]: vals sorted.  All decreasing.
+ * Host pointers; staged through scratch_dev (device, >= n_cases*3584 bytes); synchronises.
  */
 DBA_API int dba_debug_wave_select(int n_cases, const uint64_t *keys_host, const float *vals_host,
                                   uint64_t *out_host, float *fout_host, void *scratch_dev,

@@ -157,7 +157,7 @@ def dba_debug_allocate(k: np.ndarray, C: np.ndarray, cnt: np.ndarray, alloc: np.
 def dba_debug_wave_select(keys: np.ndarray, vals: np.ndarray, out: np.ndarray, fout: np.ndarray,
                           scratch_dev: int, scratch_bytes: int, hip_stream: int = 0) -> int:
     n = int(keys.shape[0])
-    assert keys.shape == (n, 128) and vals.shape == (n, 64) and out.shape == (n, 192) and fout.shape == (n, 64)
+    assert keys.shape == (n, 128) and vals.shape == (n, 64) and out.shape == (n, 256) and fout.shape == (n, 64)
     return _check(load().dba_debug_wave_select(n, _host(keys, np.uint64), _host(vals, np.float32),
                                                _host(out, np.uint64), _host(fout, np.float32),
                                                scratch_dev, scratch_bytes, hip_stream or None))

@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
 // arrived and reads them with device-scope atomic loads (which bypass the non-coherent
 // caches).  No workgroup ever waits for another.
 template <int U, int FMT>
-__global__ __launch_bounds__(kBlock) void dba_step_fused_kernel(const StepParams p)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) void dba_step_fused_kernel(const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     constexpr size_t kBytes = sizeof(StreamSmem) > sizeof(MergeSmem) ? sizeof(StreamSmem) : sizeof(MergeSmem);
@@ -202,7 +202,9 @@ __global__ __launch_bounds__(kBlock) void dba_row_max_kernel(const float *__rest
 // Diagnostic: the wavefront selection primitives on caller-provided keys, one wave per case.
 // in: keys[128] per case, vals[64] per case.  out[0:64] = sort of keys[0:64];
 // out[64:128] = merge of sort(keys[0:64]) and sort(keys[64:128]); out[128:192] = the first
-// list after inserting keys[64..71] one at a time; fout[0:64] = sort of vals.
+// list after inserting keys[64..71] one at a time; out[192:256] = low word: the 64 greatest high
+// words of both sorted lists (32-bit merge), high word: the greatest high word left out;
+// fout[0:64] = sort of vals.
 __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float *vals, u64 *out,
                                        float *fout)
 {
@@ -211,14 +213,17 @@ __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float
     const int lane = lane_id();
     const u64 a = sort64_desc<u64>(keys[(size_t)i * 128 + lane]);
     const u64 b = sort64_desc<u64>(keys[(size_t)i * 128 + 64 + lane]);
-    out[(size_t)i * 192 + lane] = a;
-    out[(size_t)i * 192 + 64 + lane] = merge_desc<u64>(a, b);
+    out[(size_t)i * 256 + lane] = a;
+    out[(size_t)i * 256 + 64 + lane] = merge_desc<u64>(a, b);
     u64 l = a;
     for (int j = 0; j < 8; ++j) {
         const u64 x = keys[(size_t)i * 128 + 64 + j];
         l = insert_desc(l, x);
     }
-    out[(size_t)i * 192 + 128 + lane] = l;
+    out[(size_t)i * 256 + 128 + lane] = l;
+    uint32_t fell = 0;
+    const uint32_t hi = merge32_desc((uint32_t)(a >> 32), (uint32_t)(b >> 32), fell);
+    out[(size_t)i * 256 + 192 + lane] = ((u64)wave_max_u32(fell) << 32) | hi;
     fout[(size_t)i * 64 + lane] = float_from_ord(sort64_desc<uint32_t>(ord_from_float(vals[(size_t)i * 64 + lane])));
 }
 
@@ -773,12 +778,12 @@ DBA_API int dba_debug_wave_select(int n_cases, const uint64_t *keys_host, const 
     if (n_cases < 1 || !keys_host || !vals_host || !out_host || !fout_host || !scratch_dev)
         return fail(nullptr, DBA_EINVAL, "dba_debug_wave_select: bad argument");
     const size_t n = (size_t)n_cases;
-    if (scratch_bytes < n * (128 * 8 + 192 * 8 + 64 * 4 + 64 * 4))
+    if (scratch_bytes < n * (128 * 8 + 256 * 8 + 64 * 4 + 64 * 4))
         return fail(nullptr, DBA_ENOMEM, "dba_debug_wave_select: scratch too small");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     u64 *d_keys = static_cast<u64 *>(scratch_dev);
     u64 *d_out = d_keys + n * 128;
-    float *d_vals = reinterpret_cast<float *>(d_out + n * 192);
+    float *d_vals = reinterpret_cast<float *>(d_out + n * 256);
     float *d_fout = d_vals + n * 64;
     hipError_t e = hipMemcpyAsync(d_keys, keys_host, n * 128 * 8, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipMemcpyAsync(d_vals, vals_host, n * 64 * 4, hipMemcpyHostToDevice, s);
@@ -786,7 +791,7 @@ DBA_API int dba_debug_wave_select(int n_cases, const uint64_t *keys_host, const 
         dba_wave_select_kernel<<<dim3((unsigned)n_cases), dim3(kWave), 0, s>>>(n_cases, d_keys, d_vals, d_out, d_fout);
         e = hipGetLastError();
     }
-    if (e == hipSuccess) e = hipMemcpyAsync(out_host, d_out, n * 192 * 8, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(out_host, d_out, n * 256 * 8, hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipMemcpyAsync(fout_host, d_fout, n * 64 * 4, hipMemcpyDeviceToHost, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return fail(nullptr, DBA_EHIP, "dba_debug_wave_select: HIP error: %s", hipGetErrorString(e));

@@ -95,9 +95,12 @@ struct __attribute__((aligned(16))) HypState {
 };
 
 struct MergeSmem {
-    u64 wl[kWavesPerBlock][kWave];
+    uint32_t ws[kWavesPerBlock][kWave];      // every wave's best score images
+    uint32_t wf[kWavesPerBlock][kWave];      // and the greatest images its merges dropped
+    uint32_t ws2[kWavesPerBlock][kWave];     // every wave's best low words among tied keys
+    // every wave's own candidates from sources 1 and 3: at most k of the k best plus one per row
+    u64 gath[kWavesPerBlock][kMaxBeam + kMaxBeam / kWavesPerBlock];
     HypState hyp[kMaxBeam];
-    u64 rb[kMaxBeam];                 // every row's best, as a selection-key body
     u64 sel[kMaxBeam];
     ConsTab ct;
     u64 fbucket[kMaxCons];            // phrases by the low six bits of their first token
@@ -726,6 +729,49 @@ __device__ __forceinline__ int nmet_after(int nmet, int ip, int iq, bool is_next
     return base + ((match & inc) ? 1 : 0);
 }
 
+// The 64 greatest 32-bit keys of the rows of one wave (row i of the wave = list(i), a
+// decreasing list; rows are dealt out to the waves in turn, those from k on are empty).  Two
+// chains of merges run side by side, so that their instructions interleave, and are joined at
+// the end.  A list whose head is below place `kth` of the chain it would join cannot change
+// places 0..kth of the result and is skipped; apart from that the result is exact.
+template <typename List>
+__device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List list, uint32_t &fell)
+{
+    constexpr int R = kMaxBeam / kWavesPerBlock;
+    uint32_t a0 = wave < k ? list(0) : 0u;
+    uint32_t a1 = wave + kWavesPerBlock < k ? list(1) : 0u;
+#pragma unroll
+    for (int i = 2; i < R; i += 2) {
+        if (wave + i * kWavesPerBlock < k) {               // wave-uniform
+            const uint32_t s0 = list(i);
+            const uint32_t s1 = wave + (i + 1) * kWavesPerBlock < k ? list(i + 1) : 0u;
+            const uint32_t h0 = (uint32_t)__builtin_amdgcn_readlane((int)s0, 0);
+            const uint32_t h1 = (uint32_t)__builtin_amdgcn_readlane((int)s1, 0);
+            const bool n0 = h0 != 0 && h0 >= (uint32_t)__builtin_amdgcn_readlane((int)a0, kth);
+            const bool n1 = h1 != 0 && h1 >= (uint32_t)__builtin_amdgcn_readlane((int)a1, kth);
+            if (n0 || n1) {
+                a0 = merge32_desc(a0, s0, fell);
+                a1 = merge32_desc(a1, s1, fell);
+            }
+        }
+    }
+    return __builtin_amdgcn_readlane((int)a1, 0) != 0 ? merge32_desc(a0, a1, fell) : a0;
+}
+
+// The 64 greatest keys of the four waves' lists, in every wave (one barrier).
+__device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kWavesPerBlock][kWave], int wave, int lane,
+                                                 uint32_t mine, uint32_t &fell)
+{
+    buf[wave][lane] = mine;
+    __syncthreads();
+    const uint32_t o1 = buf[(wave + 1) & (kWavesPerBlock - 1)][lane];
+    const uint32_t o2 = buf[(wave + 2) & (kWavesPerBlock - 1)][lane];
+    const uint32_t o3 = buf[(wave + 3) & (kWavesPerBlock - 1)][lane];
+    const uint32_t x = merge32_desc(mine, o1, fell);
+    const uint32_t y = merge32_desc(o2, o3, fell);
+    return merge32_desc(x, y, fell);
+}
+
 // COHERENT: the row lists were written by other workgroups of the same launch and are read
 // with device-scope atomic loads (see dba_step_fused_kernel).
 template <bool COHERENT>
@@ -796,71 +842,94 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         sm.hyp[tid] = hs;
     }
 
-    // ---- source 1: the sentence's k best (Sec. 3.1 item 1) = top k of the union of the
-    // row lists; source 3: every row's best (item 3) = the head of its list.  A list whose
-    // head does not beat the running k-th best cannot contribute and is skipped. -----------
-    u64 acc = 0;
-#pragma unroll
-    for (int i = 0; i < kRowsPerWave; ++i) {
-        const int h = wave + i * kWavesPerBlock;
-        if (h < k) {                                   // wave-uniform
-            if (lane == 0) sm.rb[h] = body_from_rowkey(mb, rl[i]);
-            if (i == 0) acc = rl[0];
-            else if (read_lane(rl[i], 0) > read_lane(acc, k - 1)) acc = merge_desc<u64, true>(acc, rl[i]);
-        }
-    }
-    sm.wl[wave][lane] = acc;
-    __syncthreads();                                   // tables, beam and partial lists are in LDS
-
+    // ---- source 1: the sentence's k best (Sec. 3.1 item 1) = top k of the union of the row
+    // lists.  All that is needed of them is the bar tau a key has to reach to be among them.
+    // The k-th best SCORE comes from merging the 32-bit score images alone.  If the keys with
+    // that score or a better one are exactly k, that is the bar.  Otherwise several keys tie
+    // for the last places: the same merge over the low words (the coordinates, complemented)
+    // of the keys with that score finds the last one that gets in. -------------------------
+    uint32_t fell = 0;
+    uint32_t accs = wave_best64(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> 32); }, fell);
+    sm.wf[wave][lane] = fell;
+    accs = block_best64(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
     const int C = sm.ct.poff[P];
-    for (int w = 1; w < kWavesPerBlock; ++w) {
-        const u64 other = sm.wl[(wave + w) & (kWavesPerBlock - 1)][lane];
-        if (read_lane(other, 0) > read_lane(acc, k - 1)) acc = merge_desc<u64, true>(acc, other);
+    // every wave now holds the sentence's best score images, lane i = i-th best
+    const uint32_t tau_s = (uint32_t)__builtin_amdgcn_readlane((int)accs, k - 1);
+    bool settled = true;
+    if (tau_s != 0) {
+        settled = __popcll(__ballot(accs >= tau_s)) == k;  // places k.. hold lower scores
+        if (settled && k == kWave) {
+            // every place is taken: a tie may hide among the keys the merges dropped
+            for (int w = 1; w < kWavesPerBlock; ++w) {
+                const uint32_t f = sm.wf[(wave + w) & (kWavesPerBlock - 1)][lane];
+                fell = fell > f ? fell : f;
+            }
+            settled = wave_max_u32(fell) < tau_s;
+        }
     }
-    // every wave now holds the sentence's best keys, lane i = i-th best.
-    // tau = k-th best; 0 while fewer than k finite sums exist, in which case every finite sum
-    // is among the k best already.
-    const u64 tau = body_from_rowkey(mb, read_lane(acc, k - 1));
+    // tau = what a selection-key body has to reach to be among the k best; 0 while fewer than
+    // k finite sums exist, in which case every finite sum is among them.
+    u64 tau = (u64)tau_s << fb;
+    if (!settled) {                                        // the same decision in every wave
+        const int need = k - __popcll(__ballot(accs > tau_s));      // places left for the tied keys
+        uint32_t unused = 0;
+        uint32_t accl = wave_best64(wave, k, need - 1, [&](int i) {
+            // the tied keys of a decreasing list are neighbours: move them to the front
+            const uint32_t hi = (uint32_t)(rl[i] >> 32);
+            const int first = __popcll(__ballot(hi > tau_s));
+            const uint32_t lo = hi == tau_s ? (uint32_t)rl[i] : 0u;
+            const uint32_t moved = (uint32_t)__shfl((int)lo, (lane + first) & (kWave - 1), kWave);
+            return lane + first < kWave ? moved : 0u;
+        }, unused);
+        accl = block_best64(sm.ws2, wave, lane, accl, unused);
+        const uint32_t tau_l = (uint32_t)__builtin_amdgcn_readlane((int)accl, need - 1);
+        tau = body_from_rowkey(mb, ((u64)tau_s << 32) | tau_l);
+    }
 
-    // ---- candidates, deduplicated by construction: the k best; a row's best unless among
-    // the k best; an expandable constraint token (item 2) unless among the k best or equal
-    // to its row's best (the table never offers one token twice for a hypothesis).  A wave
-    // counts its candidates, reserves room with one atomic and writes them. ---------------
-    u64 g_body = 0;
-    int g_bank = 0;
-    bool g_valid = false;
-    if (wave <= 1) {
-        // wave 0: the k best; wave 1: the rows' best.  Their bank needs add() (Sec. 3.1).
-        g_body = lane < k ? (wave == 0 ? body_from_rowkey(mb, acc) : sm.rb[lane]) : 0ull;
-        g_valid = g_body != 0 && (wave == 0 || (tau != 0 && g_body < tau));
-        int h = 0, w = -1;
-        if (g_valid) {
-            const uint32_t code = flatmask - ((uint32_t)g_body & flatmask);
-            h = (int)(code >> p.tok_bits);
-            w = (int)(code & tokmask);
-        }
-        const HypState hs = sm.hyp[h];
-        const u64 match = first_token_matches(w, sm);
-        if (g_valid) {
-            g_bank = hs.misc >> 8;
-            if (!(hs.misc & kFinFinished))
-                g_bank = nmet_after(g_bank, hs.ipq < 0 ? -1 : (hs.ipq >> 8), hs.ipq < 0 ? 0 : (hs.ipq & 255),
-                                    w == hs.nxt, match, hs.inc);
-        }
-    }
-    int total = __popcll(__ballot(g_valid));
+    // ---- candidates, deduplicated by construction: the k best; a row's best (item 3, the
+    // head of its list) unless among the k best; an expandable constraint token (item 2)
+    // unless among the k best or equal to its row's best (the table never offers one token
+    // twice for a hypothesis).  Each wave collects what its own rows give to sources 1 and 3
+    // (in a decreasing list the keys that reach tau come first), works out their banks with
+    // add() (Sec. 3.1), counts its candidates, reserves room with one atomic and writes them.
+    int n13 = 0;
     u64 rbv[kRowsPerWave];
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) {
         const int h = wave + i * kWavesPerBlock;
-        rbv[i] = h < k ? sm.rb[h] : 0ull;
+        rbv[i] = 0;
+        if (h < k) {
+            const u64 body = body_from_rowkey(mb, rl[i]);
+            const int among = __popcll(__ballot(body != 0 && body >= tau));
+            rbv[i] = read_lane(body, 0);
+            const int n = among > 0 ? among : (rbv[i] != 0 ? 1 : 0);
+            if (lane < n) sm.gath[wave][n13 + lane] = body;
+            n13 += n;
+        }
     }
+    int total = n13;
+    // where tau stands for a score alone, a constraint token with exactly that score is among
+    // the k best only if its row's list holds it (every listed key with that score is)
+    const bool by_score = settled && tau_s != 0;
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) {
         const int h = wave + i * kWavesPerBlock;
         if (h < k) {
             const u64 body = ck[i] & body_mask;
-            const bool valid = ck[i] != 0 && tau != 0 && body < tau && body != rbv[i];
+            bool below = body < tau;
+            if (by_score) {
+                u64 tied = __ballot(ck[i] != 0 && (uint32_t)(body >> fb) == tau_s);
+                if (tied) {
+                    const u64 listed = body_from_rowkey(mb, rl[i]);
+                    do {
+                        const int l = __ffsll((long long)tied) - 1;
+                        tied &= tied - 1;
+                        const u64 one = read_lane(body, l);
+                        if (__ballot(listed == one) == 0 && lane == l) below = true;
+                    } while (tied);
+                }
+            }
+            const bool valid = ck[i] != 0 && tau != 0 && below && body != rbv[i];
             if (!valid) ck[i] = 0;
             total += __popcll(__ballot(valid));
         }
@@ -868,15 +937,29 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     int at = 0;
     if (lane == 0 && total > 0) at = atomicAdd(&sm.ncand, total);
     at = __builtin_amdgcn_readfirstlane(at);
-    {
-        const u64 m = __ballot(g_valid);
-        if (g_valid) {
-            cand[at + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u))] =
-                mb ? (g_body | ((u64)g_bank << sel_shift)) : g_body;
-            atomicAdd(&sm.cnt[g_bank], 1);             // bank = constraints met (Sec. 3.1)
+    __builtin_amdgcn_wave_barrier();                   // the wave reads back what its lanes wrote
+    for (int base = 0; base < n13; base += kWave) {
+        const int idx = base + lane;
+        const bool valid = idx < n13;
+        const u64 body = valid ? sm.gath[wave][idx] : 0ull;
+        int h = 0, w = -1;
+        if (valid) {
+            const uint32_t code = flatmask - ((uint32_t)body & flatmask);
+            h = (int)(code >> p.tok_bits);
+            w = (int)(code & tokmask);
         }
-        at += __popcll(m);
+        const HypState hs = sm.hyp[h];
+        const u64 match = first_token_matches(w, sm);
+        if (valid) {
+            int bank = hs.misc >> 8;
+            if (!(hs.misc & kFinFinished))
+                bank = nmet_after(bank, hs.ipq < 0 ? -1 : (hs.ipq >> 8), hs.ipq < 0 ? 0 : (hs.ipq & 255),
+                                  w == hs.nxt, match, hs.inc);
+            cand[at + idx] = mb ? (body | ((u64)bank << sel_shift)) : body;
+            atomicAdd(&sm.cnt[bank], 1);                  // bank = constraints met (Sec. 3.1)
+        }
     }
+    at += n13;
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) {
         const int h = wave + i * kWavesPerBlock;

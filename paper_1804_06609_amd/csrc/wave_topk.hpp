@@ -186,6 +186,49 @@ __device__ __forceinline__ T merge_desc(T a, T b)
     return bitonic_finish_desc<T, 64, LL>(a > b_rev ? a : b_rev);   // bitonic, holds the top 64
 }
 
+// ---- 32-bit keys on the integer min/max units -------------------------------------------
+// A compare-exchange stage on 32-bit keys is two min/max instructions (the lane exchange rides
+// on them as a DPP operand where one DPP move does it) and a select by the lane's constant
+// role: half the issue slots of the 64-bit stage above and no trip through the scalar unit.
+// Equal keys are allowed.
+template <int J>
+__device__ __forceinline__ uint32_t clean32_desc(uint32_t v)
+{
+    const uint32_t o = xor_lane_u32<J, true>(v);
+    const uint32_t mx = v > o ? v : o, mn = v > o ? o : v;
+    return (lane_id() & J) ? mn : mx;
+}
+
+// a, b: decreasing lists of 32-bit keys.  Returns the 64 greatest of their union, decreasing;
+// `fell` collects, lane by lane, the greatest key that did not make it.
+__device__ __forceinline__ uint32_t merge32_desc(uint32_t a, uint32_t b, uint32_t &fell)
+{
+    const uint32_t b_rev = flip_lane_u32<64, true>(b);
+    const uint32_t lo = a > b_rev ? b_rev : a;
+    uint32_t v = a > b_rev ? a : b_rev;                  // bitonic, holds the top 64
+    fell = fell > lo ? fell : lo;
+    v = clean32_desc<32>(v);
+    v = clean32_desc<16>(v);
+    v = clean32_desc<8>(v);
+    v = clean32_desc<4>(v);
+    v = clean32_desc<2>(v);
+    v = clean32_desc<1>(v);
+    return v;
+}
+
+// greatest value of v over the wave, in every lane
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    uint32_t o;
+    o = xor_lane_u32<1, true>(v); v = v > o ? v : o;
+    o = xor_lane_u32<2, true>(v); v = v > o ? v : o;
+    o = xor_lane_u32<4, true>(v); v = v > o ? v : o;
+    o = xor_lane_u32<8, true>(v); v = v > o ? v : o;
+    o = xor_lane_u32<16, true>(v); v = v > o ? v : o;
+    o = xor_lane_u32<32, true>(v); v = v > o ? v : o;
+    return v;
+}
+
 // Insert the wave-uniform key x (x != 0, not already present) into a decreasing list;
 // the smallest entry falls off the end.
 __device__ __forceinline__ u64 insert_desc(u64 list, u64 x)

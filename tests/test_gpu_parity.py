@@ -67,7 +67,8 @@ def test_allocation_device_matches_oracle(torch_gpu):
 
 def test_wave_selection_primitives(torch_gpu):
     """The 64-lane sort / merge / insert networks (DPP and permlane exchanges) against a host
-    sort, on random distinct keys, keys differing only in the low word, and sentinels."""
+    sort, on random distinct keys, keys differing only in the low word, and sentinels; the 32-bit
+    merge on the keys' high words (all equal in every fourth case)."""
     import paper_1804_06609_amd as dba
     n = 512
     rng = np.random.default_rng(7)
@@ -80,9 +81,9 @@ def test_wave_selection_primitives(torch_gpu):
     vals = rng.standard_normal((n, 64)).astype(np.float32) * 10
     vals[5::8, 10:30] = -np.inf
     vals[6::8, :] = np.float32(-3.25)
-    out = np.zeros((n, 192), np.uint64)
+    out = np.zeros((n, 256), np.uint64)
     fout = np.zeros((n, 64), np.float32)
-    scratch = torch_gpu.empty(n * 3072, dtype=torch_gpu.uint8, device="cuda")
+    scratch = torch_gpu.empty(n * 3584, dtype=torch_gpu.uint8, device="cuda")
     dba.dba_debug_wave_select(keys, vals, out, fout, scratch.data_ptr(), scratch.numel(),
                               torch_gpu.cuda.current_stream().cuda_stream)
     for i in range(n):
@@ -94,6 +95,9 @@ def test_wave_selection_primitives(torch_gpu):
         if (keys[i, 64:72] != 0).all():
             assert (out[i, 128:192] == ins).all(), i
         assert fout[i].tobytes() == np.sort(vals[i])[::-1].tobytes(), i
+        hi = np.sort(keys[i] >> np.uint64(32))[::-1]
+        assert ((out[i, 192:] & np.uint64(0xFFFFFFFF)) == hi[:64]).all(), i
+        assert ((out[i, 192:] >> np.uint64(32)) == hi[64]).all(), i
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -149,14 +153,34 @@ class _TieHeavy(si.Workload):
         return lp
 
 
-@pytest.mark.parametrize("levels,fmt", [(3, None), (1, None), (6, "bf16"), (2, "f16")])
-def test_ties_everywhere(torch_gpu, levels, fmt):
-    base = si.make_small(5151 + levels, 3, 12, 6007, 9, max_phrases=4, max_len=3, dup_prob=0.3)
+@pytest.mark.parametrize("levels,fmt,k", [(3, None, 12), (1, None, 12), (6, "bf16", 12), (2, "f16", 12),
+                                          (2, None, 64), (5, "bf16", 64), (3, None, 33), (1, None, 4)])
+def test_ties_everywhere(torch_gpu, levels, fmt, k):
+    """Also the beam sizes at which the last places of the k best are contested among keys that
+    the 32-bit merges of the merge phase cannot tell apart (k = 64: every place of the lists is
+    taken, the tie shows only in what was dropped)."""
+    base = si.make_small(5151 + levels, 3, k, 6007, 9, max_phrases=4, max_len=3, dup_prob=0.3)
     wl = _TieHeavy(B=base.B, k=base.k, V=base.V, T=base.T, seed=base.seed, constraints=base.constraints,
                    boost_tokens=base.boost_tokens, boost_value=4.0, boost_prob=0.35)
     wl.levels = levels
     wl.eos_switch = 5
     _harness().run_parity(wl, logp_format=fmt)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_ties_fuzz(torch_gpu, seed):
+    """Tie-heavy decodes over beam sizes, vocabularies and tie densities: the last places of the
+    k best, the rows' bests and the constraint tokens are all contested by equal sums."""
+    rs = si.Stream(seed, 77)
+    k = [2, 5, 20, 48, 64, 63, 16, 32][seed % 8]
+    V = [300, 2000, 900, 4100][(seed // 2) % 4]
+    base = si.make_small(8800 + seed, 2, k, V, 6, max_phrases=5, max_len=3, dup_prob=0.3)
+    wl = _TieHeavy(B=base.B, k=base.k, V=base.V, T=base.T, seed=base.seed, constraints=base.constraints,
+                   boost_tokens=base.boost_tokens, boost_value=float(rs.randint(0, 3)) * 8.0 / 3.0,
+                   boost_prob=0.5)
+    wl.levels = [1, 2, 3, 4, 8, 16][rs.randint(0, 5)]
+    wl.eos_switch = 3
+    _harness().run_parity(wl, logp_format=[None, None, "bf16", "f16"][rs.randint(0, 3)])
 
 
 class _Masked(si.Workload):
