@@ -94,9 +94,11 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
     const int fin_wave = (int)((blockIdx.x >> 8) & (unsigned)(nwaves - 1));
     const u64 acc = finish_row(sm, st.list, parked, wave, nwaves, fin_wave);
     if (wave == fin_wave) {
+        // handed on in the form the merge phase works with (same order)
+        const u64 out = body_from_rowkey(p.met_bits, acc);
         u64 *dst = p.rowlists + (size_t)row * kWave + lane;
-        if (PUBLISH) __hip_atomic_store(dst, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        else *dst = acc;
+        if (PUBLISH) __hip_atomic_store(dst, out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else *dst = out;
     }
 }
 
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
 // arrival counter with a device-scope atomic.  Whoever reads k-1 there knows all k rows have
 // arrived and reads them with device-scope atomic loads (which bypass the non-coherent
 // caches).  No workgroup ever waits for another.
-template <int U, int FMT>
+template <int U, int FMT, int ROWS>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) void dba_step_fused_kernel(const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
@@ -139,15 +141,16 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) voi
     }
     __syncthreads();
     if (!last) return;
-    merge_phase<true>(p, b, *reinterpret_cast<MergeSmem *>(raw), reinterpret_cast<u64 *>(dyn_smem));
+    merge_phase<ROWS, true>(p, b, *reinterpret_cast<MergeSmem *>(raw), reinterpret_cast<u64 *>(dyn_smem));
 }
 
 // Merge phase.  Grid: one workgroup per sentence.
+template <int ROWS>
 __global__ __launch_bounds__(kBlock) void dba_merge_kernel(const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ MergeSmem sm;
-    merge_phase<false>(p, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
+    merge_phase<ROWS, false>(p, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
 }
 
 // Reference read: the largest element of each row, one workgroup per row, with the tile order and
@@ -426,6 +429,24 @@ T *at(dba_ctx *c, size_t off)
 
 }  // namespace
 
+template <int FMT>
+static void launch_fused_fmt(int rows, dim3 grid, dim3 block, size_t dyn, hipStream_t st, const StepParams &p)
+{
+    if (rows == 4) dba_step_fused_kernel<kTileLoads, FMT, 4><<<grid, block, dyn, st>>>(p);
+    else if (rows == 8) dba_step_fused_kernel<kTileLoads, FMT, 8><<<grid, block, dyn, st>>>(p);
+    else dba_step_fused_kernel<kTileLoads, FMT, 16><<<grid, block, dyn, st>>>(p);
+}
+
+static void launch_fused(int logp_format, int rows, dim3 grid, dim3 block, size_t dyn, hipStream_t st,
+                         const StepParams &p)
+{
+    switch (logp_format) {
+        case DBA_LOGP_F16: launch_fused_fmt<kFmtF16>(rows, grid, block, dyn, st, p); break;
+        case DBA_LOGP_BF16: launch_fused_fmt<kFmtBF16>(rows, grid, block, dyn, st, p); break;
+        default: launch_fused_fmt<kFmtF32>(rows, grid, block, dyn, st, p); break;
+    }
+}
+
 extern "C" {
 
 DBA_API size_t dba_workspace_bytes(int B, int k, int V, int N, int max_cons_tokens)
@@ -632,19 +653,20 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
     // 4 wavefronts per row, 4 loads of 16 bytes per lane and tile: 1280 rows x 4 waves fill the 1024 SIMDs
     // five deep with two 4 KB tiles in flight per wave (measured best on MI355X at V = 32000)
     const dim3 grid((unsigned)(c->B * c->k)), block(kBlock);
+    // the merge phase is compiled for 4, 8 and 16 beam rows per wave: the smallest that holds k
+    const int rows = c->k <= 16 ? 4 : (c->k <= 32 ? 8 : 16);
     if (c->fused) {
-        switch (logp_format) {
-            case DBA_LOGP_F16: dba_step_fused_kernel<kTileLoads, kFmtF16><<<grid, block, c->dyn_smem, c->stream>>>(p); break;
-            case DBA_LOGP_BF16: dba_step_fused_kernel<kTileLoads, kFmtBF16><<<grid, block, c->dyn_smem, c->stream>>>(p); break;
-            default: dba_step_fused_kernel<kTileLoads, kFmtF32><<<grid, block, c->dyn_smem, c->stream>>>(p); break;
-        }
+        launch_fused(logp_format, rows, grid, block, c->dyn_smem, c->stream, p);
     } else {
         switch (logp_format) {
             case DBA_LOGP_F16: dba_stream_kernel<kTileLoads, kFmtF16><<<grid, block, 0, c->stream>>>(p); break;
             case DBA_LOGP_BF16: dba_stream_kernel<kTileLoads, kFmtBF16><<<grid, block, 0, c->stream>>>(p); break;
             default: dba_stream_kernel<kTileLoads, kFmtF32><<<grid, block, 0, c->stream>>>(p); break;
         }
-        dba_merge_kernel<<<dim3((unsigned)c->B), block, c->dyn_smem, c->stream>>>(p);
+        const dim3 mgrid((unsigned)c->B);
+        if (rows == 4) dba_merge_kernel<4><<<mgrid, block, c->dyn_smem, c->stream>>>(p);
+        else if (rows == 8) dba_merge_kernel<8><<<mgrid, block, c->dyn_smem, c->stream>>>(p);
+        else dba_merge_kernel<16><<<mgrid, block, c->dyn_smem, c->stream>>>(p);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_step: launch failed: %s", hipGetErrorString(e));

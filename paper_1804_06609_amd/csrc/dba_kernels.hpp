@@ -65,7 +65,7 @@ struct StepParams {
     const u64 *same_first_lower;      // [B,64] phrase j: the lower phrases with the same first token
     const u64 *first_bucket;          // [B,64] bucket w & 63: the phrases whose first token has these low six bits
     // scratch
-    u64 *rowlists;                    // [B*k,64] sorted top keys of every row (score image, ~flat)
+    u64 *rowlists;                    // [B*k,64] every row's best sums, decreasing, as selection-key bodies
     u64 *conskeys;                    // [B*k,64] selection keys (bank, score image, ~flat) of the
                                       //          row's expandable constraint tokens, 0 = none
     unsigned int *counters;           // [B] rows of the sentence that have delivered their list
@@ -694,7 +694,7 @@ __device__ __forceinline__ u64 pack_sel(int met_bits, int bank, uint32_t ord, ui
     return v;
 }
 
-// rowlist key (score image << 32 | ~flat) -> body of a selection key (score image << fb | ~flat
+// stream-phase key (score image << 32 | ~flat) -> body of a selection key (score image << fb | ~flat
 // in fb bits); order-preserving; 0 stays 0
 __device__ __forceinline__ u64 body_from_rowkey(int met_bits, u64 key)
 {
@@ -734,23 +734,26 @@ __device__ __forceinline__ int nmet_after(int nmet, int ip, int iq, bool is_next
 // chains of merges run side by side, so that their instructions interleave, and are joined at
 // the end.  A list whose head is below place `kth` of the chain it would join cannot change
 // places 0..kth of the result and is skipped; apart from that the result is exact.
-template <typename List>
+template <int R, typename List>
 __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List list, uint32_t &fell)
 {
-    constexpr int R = kMaxBeam / kWavesPerBlock;
     uint32_t a0 = wave < k ? list(0) : 0u;
-    uint32_t a1 = wave + kWavesPerBlock < k ? list(1) : 0u;
+    uint32_t a1 = (R > 1 && wave + kWavesPerBlock < k) ? list(R > 1 ? 1 : 0) : 0u;
 #pragma unroll
     for (int i = 2; i < R; i += 2) {
         if (wave + i * kWavesPerBlock < k) {               // wave-uniform
             const uint32_t s0 = list(i);
-            const uint32_t s1 = wave + (i + 1) * kWavesPerBlock < k ? list(i + 1) : 0u;
+            const uint32_t s1 = (i + 1 < R && wave + (i + 1) * kWavesPerBlock < k) ? list(i + 1 < R ? i + 1 : i) : 0u;
             const uint32_t h0 = (uint32_t)__builtin_amdgcn_readlane((int)s0, 0);
             const uint32_t h1 = (uint32_t)__builtin_amdgcn_readlane((int)s1, 0);
             const bool n0 = h0 != 0 && h0 >= (uint32_t)__builtin_amdgcn_readlane((int)a0, kth);
             const bool n1 = h1 != 0 && h1 >= (uint32_t)__builtin_amdgcn_readlane((int)a1, kth);
-            if (n0 || n1) {
+            if (n0 && n1) {
                 a0 = merge32_desc(a0, s0, fell);
+                a1 = merge32_desc(a1, s1, fell);
+            } else if (n0) {
+                a0 = merge32_desc(a0, s0, fell);
+            } else if (n1) {
                 a1 = merge32_desc(a1, s1, fell);
             }
         }
@@ -772,12 +775,15 @@ __device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kWavesPerBlock]
     return merge32_desc(x, y, fell);
 }
 
+// ROWS: beam rows per wave the code is laid out for (k <= 4 * ROWS): the loops over a wave's rows
+// are unrolled, so a smaller bound keeps the code of small beams short.
 // COHERENT: the row lists were written by other workgroups of the same launch and are read
 // with device-scope atomic loads (see dba_step_fused_kernel).
-template <bool COHERENT>
+template <int ROWS, bool COHERENT>
 __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSmem &sm, u64 *cand)
 {
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // in a scalar register: row guards are scalar branches
     const int k = p.k, mb = p.met_bits;
     const int sel_shift = 64 - mb;
     const u64 body_mask = mb ? ((1ull << sel_shift) - 1ull) : ~0ull;
@@ -800,7 +806,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const int ld_nxt = p.nxt_cur[rs];
     const int ld_len = p.len_cur[rs];
     const int ld_fin = p.fin_cur[rs];
-    constexpr int kRowsPerWave = kMaxBeam / kWavesPerBlock;
+    constexpr int kRowsPerWave = ROWS;
     u64 rl[kRowsPerWave], ck[kRowsPerWave];
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) {
@@ -818,6 +824,10 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             }
         }
     }
+    // every load above is on its way before anything waits for one of them: the lists are
+    // pinned here, or their loads would be moved down to the conditional code that uses them
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) asm volatile("" : "+v"(rl[i]), "+v"(ck[i]));
     if (tid <= kMaxCons) {
         sm.ct.poff[tid] = ld_poff;
         sm.cnt[tid] = 0;
@@ -849,7 +859,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     // for the last places: the same merge over the low words (the coordinates, complemented)
     // of the keys with that score finds the last one that gets in. -------------------------
     uint32_t fell = 0;
-    uint32_t accs = wave_best64(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> 32); }, fell);
+    uint32_t accs = wave_best64<kRowsPerWave>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
     sm.wf[wave][lane] = fell;
     accs = block_best64(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
     const int C = sm.ct.poff[P];
@@ -872,18 +882,20 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     u64 tau = (u64)tau_s << fb;
     if (!settled) {                                        // the same decision in every wave
         const int need = k - __popcll(__ballot(accs > tau_s));      // places left for the tied keys
+        const uint32_t low_bias = fb < 32 ? 1u : 0u;
         uint32_t unused = 0;
-        uint32_t accl = wave_best64(wave, k, need - 1, [&](int i) {
+        uint32_t accl = wave_best64<kRowsPerWave>(wave, k, need - 1, [&](int i) {
             // the tied keys of a decreasing list are neighbours: move them to the front
-            const uint32_t hi = (uint32_t)(rl[i] >> 32);
+            // (a low word may be 0 where it has fewer than 32 bits: one is added meanwhile)
+            const uint32_t hi = (uint32_t)(rl[i] >> fb);
             const int first = __popcll(__ballot(hi > tau_s));
-            const uint32_t lo = hi == tau_s ? (uint32_t)rl[i] : 0u;
+            const uint32_t lo = hi == tau_s ? ((uint32_t)rl[i] & flatmask) + low_bias : 0u;
             const uint32_t moved = (uint32_t)__shfl((int)lo, (lane + first) & (kWave - 1), kWave);
             return lane + first < kWave ? moved : 0u;
         }, unused);
         accl = block_best64(sm.ws2, wave, lane, accl, unused);
         const uint32_t tau_l = (uint32_t)__builtin_amdgcn_readlane((int)accl, need - 1);
-        tau = body_from_rowkey(mb, ((u64)tau_s << 32) | tau_l);
+        tau = ((u64)tau_s << fb) | (u64)(tau_l - low_bias);
     }
 
     // ---- candidates, deduplicated by construction: the k best; a row's best (item 3, the
@@ -892,51 +904,59 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     // twice for a hypothesis).  Each wave collects what its own rows give to sources 1 and 3
     // (in a decreasing list the keys that reach tau come first), works out their banks with
     // add() (Sec. 3.1), counts its candidates, reserves room with one atomic and writes them.
-    int n13 = 0;
-    u64 rbv[kRowsPerWave];
+    // Lanes count what they hold themselves; two prefix sums over the wave then give every lane
+    // its places (no wave-wide vote per row).
+    const bool by_score = settled && tau_s != 0;
+    bool some_tied = false;
+    int g = 0;                                             // this lane's keys from sources 1 and 3
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) {
         const int h = wave + i * kWavesPerBlock;
-        rbv[i] = 0;
         if (h < k) {
-            const u64 body = body_from_rowkey(mb, rl[i]);
-            const int among = __popcll(__ballot(body != 0 && body >= tau));
-            rbv[i] = read_lane(body, 0);
-            const int n = among > 0 ? among : (rbv[i] != 0 ? 1 : 0);
-            if (lane < n) sm.gath[wave][n13 + lane] = body;
-            n13 += n;
+            const u64 best = read_lane(rl[i], 0);
+            g += (rl[i] != 0 && (rl[i] >= tau || lane == 0)) ? 1 : 0;
+            // where tau stands for a score alone, a constraint token with exactly that score is
+            // among the k best only if its row's list holds it (every listed key with that
+            // score is): looked up below
+            const u64 body = ck[i] & body_mask;
+            const bool tied = by_score && (uint32_t)(body >> fb) == tau_s;
+            const bool valid = ck[i] != 0 && tau != 0 && (body < tau || tied) && body != best;
+            if (!valid) ck[i] = 0;
+            some_tied |= valid && tied;
         }
     }
-    int total = n13;
-    // where tau stands for a score alone, a constraint token with exactly that score is among
-    // the k best only if its row's list holds it (every listed key with that score is)
-    const bool by_score = settled && tau_s != 0;
+    if (__ballot(some_tied)) {                             // rare
 #pragma unroll
-    for (int i = 0; i < kRowsPerWave; ++i) {
-        const int h = wave + i * kWavesPerBlock;
-        if (h < k) {
-            const u64 body = ck[i] & body_mask;
-            bool below = body < tau;
-            if (by_score) {
+        for (int i = 0; i < kRowsPerWave; ++i) {
+            const int h = wave + i * kWavesPerBlock;
+            if (h < k) {
+                const u64 body = ck[i] & body_mask;
                 u64 tied = __ballot(ck[i] != 0 && (uint32_t)(body >> fb) == tau_s);
-                if (tied) {
-                    const u64 listed = body_from_rowkey(mb, rl[i]);
-                    do {
-                        const int l = __ffsll((long long)tied) - 1;
-                        tied &= tied - 1;
-                        const u64 one = read_lane(body, l);
-                        if (__ballot(listed == one) == 0 && lane == l) below = true;
-                    } while (tied);
+                while (tied) {
+                    const int l = __ffsll((long long)tied) - 1;
+                    tied &= tied - 1;
+                    const u64 one = read_lane(body, l);
+                    if (__ballot(rl[i] == one) != 0 && lane == l) ck[i] = 0;
                 }
             }
-            const bool valid = ck[i] != 0 && tau != 0 && below && body != rbv[i];
-            if (!valid) ck[i] = 0;
-            total += __popcll(__ballot(valid));
         }
     }
+    int c = 0;                                             // this lane's keys from source 2
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i)
+        if (wave + i * kWavesPerBlock < k) c += ck[i] != 0 ? 1 : 0;
+    const int g_incl = wave_inclusive_sum(g), c_incl = wave_inclusive_sum(c);
+    const int n13 = __builtin_amdgcn_readlane(g_incl, kWave - 1);
+    const int total = n13 + __builtin_amdgcn_readlane(c_incl, kWave - 1);
     int at = 0;
     if (lane == 0 && total > 0) at = atomicAdd(&sm.ncand, total);
     at = __builtin_amdgcn_readfirstlane(at);
+    {
+        int to = g_incl - g;
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i)
+            if (wave + i * kWavesPerBlock < k && rl[i] != 0 && (rl[i] >= tau || lane == 0)) sm.gath[wave][to++] = rl[i];
+    }
     __builtin_amdgcn_wave_barrier();                   // the wave reads back what its lanes wrote
     for (int base = 0; base < n13; base += kWave) {
         const int idx = base + lane;
@@ -959,17 +979,14 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             atomicAdd(&sm.cnt[bank], 1);                  // bank = constraints met (Sec. 3.1)
         }
     }
-    at += n13;
+    {
+        int to = at + n13 + c_incl - c;
 #pragma unroll
-    for (int i = 0; i < kRowsPerWave; ++i) {
-        const int h = wave + i * kWavesPerBlock;
-        if (h < k) {
-            const u64 m = __ballot(ck[i] != 0);
-            if (ck[i] != 0) {
-                cand[at + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u))] = ck[i];
+        for (int i = 0; i < kRowsPerWave; ++i) {
+            if (wave + i * kWavesPerBlock < k && ck[i] != 0) {
+                cand[to++] = ck[i];
                 atomicAdd(&sm.cnt[mb ? (int)(ck[i] >> sel_shift) : 0], 1);
             }
-            at += __popcll(m);
         }
     }
     __syncthreads();
@@ -993,8 +1010,8 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     }
     // ---- every candidate's place in the order (bank desc, score desc, coordinate asc):
     // chunks of 64 are sorted by one wave each (wave 0, busy with the allocation, last); a
-    // candidate's rank is its place in its own chunk plus, by binary search, the keys greater
-    // than it in every other chunk ------------------------------------------------------------
+    // candidate's rank is its place in its own chunk plus, by a search with three probes a round,
+    // the keys greater than it in every other chunk ------------------------------------------------------------
     const int my_first = kWavesPerBlock - 1 - wave;
     for (int c = my_first; c < nchunks; c += kWavesPerBlock) {
         const int i = c * kWave + lane;
@@ -1014,12 +1031,17 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
                 pos[q] = 0;
                 full[q] = cand[c2 * kWave + 63] > mine;
             }
+            // three probes a round (quarters, then sixteenths, then single places): three
+            // dependent trips to LDS instead of six
 #pragma unroll
-            for (int step = 32; step >= 1; step >>= 1) {
+            for (int step = 16; step >= 1; step >>= 2) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int c2 = c0 + q < nchunks ? c0 + q : c;
-                    if (cand[c2 * kWave + pos[q] + step - 1] > mine) pos[q] += step;
+                    const u64 *at0 = cand + c2 * kWave + pos[q] - 1;
+                    const int above = (at0[step] > mine ? 1 : 0) + (at0[2 * step] > mine ? 1 : 0) +
+                                      (at0[3 * step] > mine ? 1 : 0);
+                    pos[q] += step * above;
                 }
             }
 #pragma unroll
