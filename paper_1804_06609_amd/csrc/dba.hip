@@ -333,7 +333,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
     size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2];
-    size_t cons_tok, phr_off, nphr, ftok, sfl, bloom, rowlists, conskeys, counters;
+    size_t cons_tok, phr_off, nphr, ftok, sfl, bloom, btok, rowlists, conskeys, counters;
     size_t hist_token, hist_backptr;
     size_t fin_tokens, fin_len, fin_score, fin_status, all_finished;
     size_t total;
@@ -363,6 +363,7 @@ Layout make_layout(size_t B, size_t k, size_t N)
     L.ftok = take(B * kMaxCons * sizeof(int32_t));
     L.sfl = take(B * kMaxCons * sizeof(u64));
     L.bloom = take(B * kMaxCons * sizeof(u64));
+    L.btok = take(B * kMaxCons * sizeof(int32_t));
     L.rowlists = take(B * k * kWave * sizeof(u64));
     L.conskeys = take(B * k * kMaxCons * sizeof(u64));
     L.counters = take(B * sizeof(unsigned int));
@@ -483,7 +484,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
             return fail(nullptr, DBA_EINVAL, "dba_init: sent_offsets decreases at %d", b);
     std::vector<int32_t> tok((size_t)B * kMaxCons, 0), off((size_t)B * (kMaxCons + 1), 0), nph(B, 0);
     std::vector<u64> sfl((size_t)B * kMaxCons, 0), bloom((size_t)B * kMaxCons, 0);
-    std::vector<int32_t> ftok((size_t)B * kMaxCons, -1);
+    std::vector<int32_t> ftok((size_t)B * kMaxCons, -1), btok((size_t)B * kMaxCons, -1);
     int max_tokens = 0, max_phrases = 0;
     for (int b = 0; b < B; ++b) {
         const int p0 = sent_offsets[b], p1 = sent_offsets[b + 1];
@@ -511,11 +512,14 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         off[(size_t)b * (kMaxCons + 1) + (p1 - p0)] = n;
         nph[b] = p1 - p0;
         // lookup aids for the kernels (layout only): which lower phrases share a phrase's first
-        // token, and the phrases bucketed by the low six bits of their first token
+        // token; the phrases bucketed by the low six bits of their first token; and that token
+        // itself where all phrases of a bucket begin alike (-1 empty bucket, -2 they differ)
         for (int j = 0; j < p1 - p0; ++j) {
             const int fj = tok[(size_t)b * kMaxCons + off[(size_t)b * (kMaxCons + 1) + j]];
             ftok[(size_t)b * kMaxCons + j] = fj;
             bloom[(size_t)b * kMaxCons + (fj & 63)] |= 1ull << j;
+            int32_t &bt = btok[(size_t)b * kMaxCons + (fj & 63)];
+            bt = bt == -1 ? fj : (bt == fj ? fj : -2);
             for (int j2 = 0; j2 < j; ++j2)
                 if (tok[(size_t)b * kMaxCons + off[(size_t)b * (kMaxCons + 1) + j2]] == fj)
                     sfl[(size_t)b * kMaxCons + j] |= 1ull << j2;
@@ -569,6 +573,8 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
         e = hipMemcpyAsync(at<u64>(c, L.sfl), sfl.data(), sfl.size() * 8, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess)
         e = hipMemcpyAsync(at<u64>(c, L.bloom), bloom.data(), bloom.size() * 8, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(at<int32_t>(c, L.btok), btok.data(), btok.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) {
         const int n = B * k;
         dba_init_state_kernel<<<(n + 255) / 256, 256, 0, c->stream>>>(
@@ -638,6 +644,7 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
     p.first_tok = at<int32_t>(c, L.ftok);
     p.same_first_lower = at<u64>(c, L.sfl);
     p.first_bucket = at<u64>(c, L.bloom);
+    p.bucket_tok = at<int32_t>(c, L.btok);
     p.rowlists = at<u64>(c, L.rowlists);
     p.conskeys = at<u64>(c, L.conskeys);
     p.counters = at<unsigned int>(c, L.counters);

@@ -64,6 +64,7 @@ struct StepParams {
     const int32_t *first_tok;         // [B,64] first token of phrase j
     const u64 *same_first_lower;      // [B,64] phrase j: the lower phrases with the same first token
     const u64 *first_bucket;          // [B,64] bucket w & 63: the phrases whose first token has these low six bits
+    const int32_t *bucket_tok;        // [B,64] that first token if the bucket's phrases agree on it; -1 none, -2 they differ
     // scratch
     u64 *rowlists;                    // [B*k,64] every row's best sums, decreasing, as selection-key bodies
     u64 *conskeys;                    // [B*k,64] selection keys (bank, score image, ~flat) of the
@@ -104,6 +105,7 @@ struct MergeSmem {
     u64 sel[kMaxBeam];
     ConsTab ct;
     u64 fbucket[kMaxCons];            // phrases by the low six bits of their first token
+    int btok[kMaxCons];               // and that token where a bucket's phrases agree on it (-1 none, -2 they differ)
     int cnt[kMaxCons + 1];
     int alloc[kMaxCons + 1];
     int start[kMaxCons + 1];
@@ -703,13 +705,16 @@ __device__ __forceinline__ u64 body_from_rowkey(int met_bits, u64 key)
 }
 
 // The phrases whose first token is w (w < 0: none), as a bit mask.  Every lane looks its own
-// token up: the bucket of the token's low six bits names the few phrases to compare with
-// (usually none or one).
+// token up in the bucket of the token's low six bits: one trip to LDS where the bucket's
+// phrases all begin with the same token (nearly always), else they are compared one by one.
 __device__ __forceinline__ u64 first_token_matches(int w, const MergeSmem &sm)
 {
+    if (w < 0) return 0;
+    const int same = sm.btok[w & 63];
+    u64 todo = sm.fbucket[w & 63];
+    if (same == w) return todo;
     u64 mine = 0;
-    if (w >= 0) {
-        u64 todo = sm.fbucket[w & 63];
+    if (same == -2) {
         while (todo) {
             const int j = __ffsll((long long)todo) - 1;
             todo &= todo - 1;
@@ -800,6 +805,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const int ld_tok = p.cons_tok[(size_t)b * kMaxCons + lane];
     const int P = p.nphr[b];
     const u64 ld_bucket = p.first_bucket[(size_t)b * kMaxCons + lane];
+    const int ld_btok = p.bucket_tok[(size_t)b * kMaxCons + lane];
     const u64 ld_met = p.met_cur[rs];
     const u64 ld_inc = p.inc_cur[rs];
     const int ld_ipq = p.ipq_cur[rs];
@@ -835,6 +841,8 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     if (tid < kMaxCons) {
         sm.ct.tok[tid] = ld_tok;
         sm.fbucket[tid] = ld_bucket;
+        sm.btok[tid] = ld_btok;
+        sm.sel[tid] = 0;                               // places beyond the last selected key compare as empty
     }
     if (tid == 0) {
         sm.ncand = 0;
@@ -1064,7 +1072,9 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         const bool live = lane < nsel;
         const u64 mine = live ? sm.sel[lane] : 0ull;
         int slot = 0;
-        for (int j = 0; j < nsel; ++j) slot += sm.sel[j] > mine ? 1 : 0;
+        for (int j = 0; j < nsel; j += 4)                 // (kMaxBeam is a multiple of 4; unused places hold 0)
+            slot += (sm.sel[j] > mine ? 1 : 0) + (sm.sel[j + 1] > mine ? 1 : 0) + (sm.sel[j + 2] > mine ? 1 : 0) +
+                    (sm.sel[j + 3] > mine ? 1 : 0);
         int token = p.pad_id, parent = -1, length = 0, ipq2 = -1, nxt2 = -1;
         float score = -INFINITY;
         u64 met2 = 0, inc2 = 0;
