@@ -32,9 +32,15 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
     const int nwaves = (int)(blockDim.x >> 6);
     const bool gatherer = wave == nwaves - 1;     // this wave also fetches the constraint tokens
 
-    // requests in the order their answers are needed: the hypothesis, its constraint
-    // bookkeeping (one wave, one lane per phrase), then the first two tiles of the row (which
-    // need nothing of the hypothesis)
+    // the first two tiles of the row are requested before anything else: they need nothing of
+    // the hypothesis, and the loads of the hypothesis (uniform, hence scalar loads the wave has to
+    // wait for one after the other) would otherwise hold them back
+    const elem_t *__restrict__ logp_row = static_cast<const elem_t *>(p.logp) + (size_t)row * (size_t)p.V;
+    RowStream<U, FMT> rs;
+    const bool known_empty = p.first_step && h != 0;   // decoder-init leaves slots 1.. empty
+    if (!known_empty) rs.begin(logp_row, p.V, wave, nwaves);
+    __builtin_amdgcn_sched_barrier(0);
+    // then the hypothesis and its constraint bookkeeping (one wave, one lane per phrase)
     const float prev_ld = p.score_cur[row];
     const int fin_ld = p.fin_cur[row];
     u64 g_met = 0, g_inc = 0, g_sfl = 0;
@@ -48,10 +54,6 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
         g_ftok = p.first_tok[(size_t)b * kMaxCons + lane];
         g_sfl = p.same_first_lower[(size_t)b * kMaxCons + lane];
     }
-    const elem_t *__restrict__ logp_row = static_cast<const elem_t *>(p.logp) + (size_t)row * (size_t)p.V;
-    RowStream<U, FMT> rs;
-    const bool known_empty = p.first_step && h != 0;   // decoder-init leaves slots 1.. empty
-    if (!known_empty) rs.begin(logp_row, p.V, wave, nwaves);
 
     // the row's hypothesis: wave-uniform by construction, made so for the compiler
     const float prev = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(prev_ld)));
