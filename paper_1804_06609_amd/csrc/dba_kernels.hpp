@@ -915,44 +915,48 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     // Lanes count what they hold themselves; two prefix sums over the wave then give every lane
     // its places (no wave-wide vote per row).
     const bool by_score = settled && tau_s != 0;
+    // a key of a row's list is kept if it reaches tau; lane 0 holds the row's best and keeps any
+    const u64 keep_from = lane == 0 ? 1ull : (tau > 1 ? tau : 1ull);
+    // a constraint token is a candidate while below tau.  Where tau stands for a score alone,
+    // one with exactly that score is among the k best only if its row's list holds it (every
+    // listed key with that score is): those pass for now and are looked up below.
+    const u64 below = by_score ? tau + (1ull << fb) : tau;
+    uint32_t gm = 0, cm = 0;                               // bit i: this lane's key of row i is kept
     bool some_tied = false;
-    int g = 0;                                             // this lane's keys from sources 1 and 3
+    if (tau != 0) {
 #pragma unroll
-    for (int i = 0; i < kRowsPerWave; ++i) {
-        const int h = wave + i * kWavesPerBlock;
-        if (h < k) {
-            const u64 best = read_lane(rl[i], 0);
-            g += (rl[i] != 0 && (rl[i] >= tau || lane == 0)) ? 1 : 0;
-            // where tau stands for a score alone, a constraint token with exactly that score is
-            // among the k best only if its row's list holds it (every listed key with that
-            // score is): looked up below
-            const u64 body = ck[i] & body_mask;
-            const bool tied = by_score && (uint32_t)(body >> fb) == tau_s;
-            const bool valid = ck[i] != 0 && tau != 0 && (body < tau || tied) && body != best;
-            if (!valid) ck[i] = 0;
-            some_tied |= valid && tied;
+        for (int i = 0; i < kRowsPerWave; ++i) {
+            if (wave + i * kWavesPerBlock < k) {
+                const u64 best = read_lane(rl[i], 0);
+                gm |= (rl[i] >= keep_from ? 1u : 0u) << i;
+                const u64 body = ck[i] & body_mask;
+                const bool valid = body - 1 < below - 1 && body != best;      // (an empty place holds 0)
+                cm |= (valid ? 1u : 0u) << i;
+                if (by_score) some_tied |= valid && body >= tau;
+            }
         }
+    } else {
+        // fewer than k finite sums: all of them are among the k best, none is left for source 2
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i)
+            if (wave + i * kWavesPerBlock < k) gm |= (rl[i] != 0 ? 1u : 0u) << i;
     }
     if (__ballot(some_tied)) {                             // rare
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
-            const int h = wave + i * kWavesPerBlock;
-            if (h < k) {
+            if (wave + i * kWavesPerBlock < k) {
                 const u64 body = ck[i] & body_mask;
-                u64 tied = __ballot(ck[i] != 0 && (uint32_t)(body >> fb) == tau_s);
+                u64 tied = __ballot(((cm >> i) & 1u) != 0 && body >= tau);
                 while (tied) {
                     const int l = __ffsll((long long)tied) - 1;
                     tied &= tied - 1;
                     const u64 one = read_lane(body, l);
-                    if (__ballot(rl[i] == one) != 0 && lane == l) ck[i] = 0;
+                    if (__ballot(rl[i] == one) != 0 && lane == l) cm &= ~(1u << i);
                 }
             }
         }
     }
-    int c = 0;                                             // this lane's keys from source 2
-#pragma unroll
-    for (int i = 0; i < kRowsPerWave; ++i)
-        if (wave + i * kWavesPerBlock < k) c += ck[i] != 0 ? 1 : 0;
+    const int g = __popc(gm), c = __popc(cm);              // this lane's keys from sources 1 and 3, from source 2
     const int g_incl = wave_inclusive_sum(g), c_incl = wave_inclusive_sum(c);
     const int n13 = __builtin_amdgcn_readlane(g_incl, kWave - 1);
     const int total = n13 + __builtin_amdgcn_readlane(c_incl, kWave - 1);
@@ -963,7 +967,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         int to = g_incl - g;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i)
-            if (wave + i * kWavesPerBlock < k && rl[i] != 0 && (rl[i] >= tau || lane == 0)) sm.gath[wave][to++] = rl[i];
+            if (wave + i * kWavesPerBlock < k && ((gm >> i) & 1u)) sm.gath[wave][to++] = rl[i];
     }
     __builtin_amdgcn_wave_barrier();                   // the wave reads back what its lanes wrote
     for (int base = 0; base < n13; base += kWave) {
@@ -991,7 +995,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         int to = at + n13 + c_incl - c;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
-            if (wave + i * kWavesPerBlock < k && ck[i] != 0) {
+            if (wave + i * kWavesPerBlock < k && ((cm >> i) & 1u)) {
                 cand[to++] = ck[i];
                 atomicAdd(&sm.cnt[mb ? (int)(ck[i] >> sel_shift) : 0], 1);
             }
