@@ -875,7 +875,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const uint32_t tau_s = (uint32_t)__builtin_amdgcn_readlane((int)accs, k - 1);
     bool settled = true;
     if (tau_s != 0) {
-        settled = __popcll(__ballot(accs >= tau_s)) == k;  // places k.. hold lower scores
+        settled = (int)__popcll(__ballot(accs >= tau_s)) == k;  // places k.. hold lower scores
         if (settled && k == kWave) {
             // every place is taken: a tie may hide among the keys the merges dropped
             for (int w = 1; w < kWavesPerBlock; ++w) {
@@ -1162,7 +1162,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             p.ipq_nxt[o] = ipq2;
             p.nxt_nxt[o] = nxt2;
             p.len_nxt[o] = length;
-            p.fin_nxt[o] = (uint8_t)(fin2 | ((!fin2 && __popcll(met2) < C) ? kFinEosBlocked : 0));
+            p.fin_nxt[o] = (uint8_t)(fin2 | ((!fin2 && (int)__popcll(met2) < C) ? kFinEosBlocked : 0));
             p.hist_token[o] = token;
             p.hist_backptr[o] = parent;
             if (p.out_token) p.out_token[o] = token;
