@@ -132,6 +132,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) voi
 
     const int row = (int)blockIdx.x;
     const int b = row / p.k;
+    // waves that stream go before waves that merge when both want to issue: a compute unit
+    // serves its oldest waves first, and those would be the merging ones
+    __builtin_amdgcn_s_setprio(2);
     stream_phase<U, FMT, true>(p, row, *reinterpret_cast<StreamSmem *>(raw));
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's published stores are done
     __syncthreads();
@@ -143,6 +146,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) voi
     }
     __syncthreads();
     if (!last) return;
+    __builtin_amdgcn_s_setprio(0);
     merge_phase<ROWS, true>(p, b, *reinterpret_cast<MergeSmem *>(raw), reinterpret_cast<u64 *>(dyn_smem));
 }
 
