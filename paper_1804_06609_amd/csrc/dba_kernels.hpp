@@ -766,7 +766,10 @@ __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List l
     return __builtin_amdgcn_readlane((int)a1, 0) != 0 ? merge32_desc(a0, a1, fell) : a0;
 }
 
-// The 64 greatest keys of the four waves' lists, in every wave (one barrier).
+// The 64 greatest keys of the four waves' lists, in every wave (one barrier).  SPARSE: most
+// lists are expected to be empty, and an empty list costs nothing; otherwise two of the three
+// merges run side by side.
+template <bool SPARSE>
 __device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kWavesPerBlock][kWave], int wave, int lane,
                                                  uint32_t mine, uint32_t &fell)
 {
@@ -775,6 +778,13 @@ __device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kWavesPerBlock]
     const uint32_t o1 = buf[(wave + 1) & (kWavesPerBlock - 1)][lane];
     const uint32_t o2 = buf[(wave + 2) & (kWavesPerBlock - 1)][lane];
     const uint32_t o3 = buf[(wave + 3) & (kWavesPerBlock - 1)][lane];
+    if (SPARSE) {
+        uint32_t acc = mine;
+        if (__builtin_amdgcn_readlane((int)o1, 0) != 0) acc = merge32_desc(acc, o1, fell);
+        if (__builtin_amdgcn_readlane((int)o2, 0) != 0) acc = merge32_desc(acc, o2, fell);
+        if (__builtin_amdgcn_readlane((int)o3, 0) != 0) acc = merge32_desc(acc, o3, fell);
+        return acc;
+    }
     const uint32_t x = merge32_desc(mine, o1, fell);
     const uint32_t y = merge32_desc(o2, o3, fell);
     return merge32_desc(x, y, fell);
@@ -869,7 +879,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     uint32_t fell = 0;
     uint32_t accs = wave_best64<kRowsPerWave>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
     sm.wf[wave][lane] = fell;
-    accs = block_best64(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
+    accs = block_best64<false>(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
     const int C = sm.ct.poff[P];
     // every wave now holds the sentence's best score images, lane i = i-th best
     const uint32_t tau_s = (uint32_t)__builtin_amdgcn_readlane((int)accs, k - 1);
@@ -896,12 +906,13 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             // the tied keys of a decreasing list are neighbours: move them to the front
             // (a low word may be 0 where it has fewer than 32 bits: one is added meanwhile)
             const uint32_t hi = (uint32_t)(rl[i] >> fb);
+            if (__ballot(hi == tau_s) == 0) return 0u;     // most rows hold none
             const int first = __popcll(__ballot(hi > tau_s));
             const uint32_t lo = hi == tau_s ? ((uint32_t)rl[i] & flatmask) + low_bias : 0u;
             const uint32_t moved = (uint32_t)__shfl((int)lo, (lane + first) & (kWave - 1), kWave);
             return lane + first < kWave ? moved : 0u;
         }, unused);
-        accl = block_best64(sm.ws2, wave, lane, accl, unused);
+        accl = block_best64<true>(sm.ws2, wave, lane, accl, unused);
         const uint32_t tau_l = (uint32_t)__builtin_amdgcn_readlane((int)accl, need - 1);
         tau = ((u64)tau_s << fb) | (u64)(tau_l - low_bias);
     }
