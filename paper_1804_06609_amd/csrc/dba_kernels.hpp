@@ -738,8 +738,8 @@ __device__ __forceinline__ int nmet_after(int nmet, int ip, int iq, bool is_next
 // decreasing list; rows are dealt out to the waves in turn, those from k on are empty).  Two
 // chains of merges run side by side, so that their instructions interleave, and are joined at
 // the end.  A list whose head is below place `kth` of the chain it would join cannot change
-// places 0..kth of the result and is skipped; apart from that the result is exact.
-template <int R, typename List>
+// places 0..kth of the result and may be skipped (LOOK); apart from that the result is exact.
+template <int R, bool LOOK, typename List>
 __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List list, uint32_t &fell)
 {
     uint32_t a0 = wave < k ? list(0) : 0u;
@@ -747,12 +747,18 @@ __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List l
 #pragma unroll
     for (int i = 2; i < R; i += 2) {
         if (wave + i * kWavesPerBlock < k) {               // wave-uniform
+            const bool pair = i + 1 < R && wave + (i + 1) * kWavesPerBlock < k;
             const uint32_t s0 = list(i);
-            const uint32_t s1 = (i + 1 < R && wave + (i + 1) * kWavesPerBlock < k) ? list(i + 1 < R ? i + 1 : i) : 0u;
-            const uint32_t h0 = (uint32_t)__builtin_amdgcn_readlane((int)s0, 0);
-            const uint32_t h1 = (uint32_t)__builtin_amdgcn_readlane((int)s1, 0);
-            const bool n0 = h0 != 0 && h0 >= (uint32_t)__builtin_amdgcn_readlane((int)a0, kth);
-            const bool n1 = h1 != 0 && h1 >= (uint32_t)__builtin_amdgcn_readlane((int)a1, kth);
+            const uint32_t s1 = pair ? list(i + 1 < R ? i + 1 : i) : 0u;
+            // LOOK: lists are looked at before they are merged (worth it where many are empty or
+            // weak); otherwise every row that exists is merged, and no value decides a branch
+            bool n0 = true, n1 = pair;
+            if (LOOK) {
+                const uint32_t h0 = (uint32_t)__builtin_amdgcn_readlane((int)s0, 0);
+                const uint32_t h1 = (uint32_t)__builtin_amdgcn_readlane((int)s1, 0);
+                n0 = h0 != 0 && h0 >= (uint32_t)__builtin_amdgcn_readlane((int)a0, kth);
+                n1 = h1 != 0 && h1 >= (uint32_t)__builtin_amdgcn_readlane((int)a1, kth);
+            }
             if (n0 && n1) {
                 a0 = merge32_desc(a0, s0, fell);
                 a1 = merge32_desc(a1, s1, fell);
@@ -763,7 +769,8 @@ __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List l
             }
         }
     }
-    return __builtin_amdgcn_readlane((int)a1, 0) != 0 ? merge32_desc(a0, a1, fell) : a0;
+    if (LOOK) return __builtin_amdgcn_readlane((int)a1, 0) != 0 ? merge32_desc(a0, a1, fell) : a0;
+    return (R > 1 && wave + kWavesPerBlock < k) ? merge32_desc(a0, a1, fell) : a0;
 }
 
 // The 64 greatest keys of the four waves' lists, in every wave (one barrier).  SPARSE: most
@@ -877,7 +884,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     // for the last places: the same merge over the low words (the coordinates, complemented)
     // of the keys with that score finds the last one that gets in. -------------------------
     uint32_t fell = 0;
-    uint32_t accs = wave_best64<kRowsPerWave>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
+    uint32_t accs = wave_best64<kRowsPerWave, false>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
     sm.wf[wave][lane] = fell;
     accs = block_best64<false>(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
     const int C = sm.ct.poff[P];
@@ -902,7 +909,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         const int need = k - __popcll(__ballot(accs > tau_s));      // places left for the tied keys
         const uint32_t low_bias = fb < 32 ? 1u : 0u;
         uint32_t unused = 0;
-        uint32_t accl = wave_best64<kRowsPerWave>(wave, k, need - 1, [&](int i) {
+        uint32_t accl = wave_best64<kRowsPerWave, true>(wave, k, need - 1, [&](int i) {
             // the tied keys of a decreasing list are neighbours: move them to the front
             // (a low word may be 0 where it has fewer than 32 bits: one is added meanwhile)
             const uint32_t hi = (uint32_t)(rl[i] >> fb);
