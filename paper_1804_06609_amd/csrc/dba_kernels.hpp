@@ -751,7 +751,8 @@ __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List l
             const uint32_t s0 = list(i);
             const uint32_t s1 = pair ? list(i + 1 < R ? i + 1 : i) : 0u;
             // LOOK: lists are looked at before they are merged (worth it where many are empty or
-            // weak); otherwise every row that exists is merged, and no value decides a branch
+            // weak, or a wave has many rows); otherwise every row that exists is merged, and no
+            // value decides a branch
             bool n0 = true, n1 = pair;
             if (LOOK) {
                 const uint32_t h0 = (uint32_t)__builtin_amdgcn_readlane((int)s0, 0);
@@ -884,7 +885,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     // for the last places: the same merge over the low words (the coordinates, complemented)
     // of the keys with that score finds the last one that gets in. -------------------------
     uint32_t fell = 0;
-    uint32_t accs = wave_best64<kRowsPerWave, false>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
+    uint32_t accs = wave_best64<kRowsPerWave, (kRowsPerWave > 8)>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
     sm.wf[wave][lane] = fell;
     accs = block_best64<false>(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
     const int C = sm.ct.poff[P];
