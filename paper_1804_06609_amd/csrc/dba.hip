@@ -626,6 +626,7 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
     p.met_bits = c->met_bits;
     p.tok_bits = c->tok_bits;
     p.first_step = c->steps == 0 ? 1 : 0;
+    p.cand_cap = (int)(c->dyn_smem / sizeof(u64));
     p.adjust = c->adjust;
     p.normalize = c->normalize;
     p.prune = c->prune;

@@ -37,6 +37,7 @@ struct StepParams {
     int met_bits;                     // width of the bank field in the packed selection key
     int tok_bits;                     // width of the token field of a coordinate: (h << tok_bits) | w
     int first_step;                   // 1: the beam is the initial one (only slot 0 of a sentence is live)
+    int cand_cap;                     // candidate keys the merge phase's dynamic LDS holds (a multiple of 64)
     int adjust;                       // 0: bank sizes stay at the base split (Sec. 5)
     int normalize;                    // 1: a hypothesis completing now is stored with sum / length (Sec. 4)
     float prune;                      // >= 0: threshold pruning against the best completed hypothesis (Sec. 4)
@@ -106,9 +107,10 @@ struct MergeSmem {
     ConsTab ct;
     u64 fbucket[kMaxCons];            // phrases by the low six bits of their first token
     int btok[kMaxCons];               // and that token where a bucket's phrases agree on it (-1 none, -2 they differ)
-    int cnt[kMaxCons + 1];
-    int alloc[kMaxCons + 1];
-    int start[kMaxCons + 1];
+    // per bank (constraints met, 0..64); sized for every value the 7-bit bank field of a key can hold
+    int cnt[2 * kMaxCons];
+    int alloc[2 * kMaxCons];
+    int start[2 * kMaxCons];
     int ncand;
     int nsel;
     u64 kept;                         // pruning: bit i = the hypothesis at place i of the new beam stays
@@ -852,9 +854,11 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     // pinned here, or their loads would be moved down to the conditional code that uses them
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) asm volatile("" : "+v"(rl[i]), "+v"(ck[i]));
-    if (tid <= kMaxCons) {
-        sm.ct.poff[tid] = ld_poff;
+    if (tid <= kMaxCons) sm.ct.poff[tid] = ld_poff;
+    if (tid < 2 * kMaxCons) {
         sm.cnt[tid] = 0;
+        sm.alloc[tid] = 0;                             // banks beyond the sentence's get no slot
+        sm.start[tid] = 0;
     }
     if (tid < kMaxCons) {
         sm.ct.tok[tid] = ld_tok;
@@ -975,14 +979,21 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             }
         }
     }
+    constexpr int kStrip = kMaxBeam + kMaxBeam / kWavesPerBlock;
     const int g = __popc(gm), c = __popc(cm);              // this lane's keys from sources 1 and 3, from source 2
     const int g_incl = wave_inclusive_sum(g), c_incl = wave_inclusive_sum(c);
-    const int n13 = __builtin_amdgcn_readlane(g_incl, kWave - 1);
-    const int total = n13 + __builtin_amdgcn_readlane(c_incl, kWave - 1);
+    const int n13_all = __builtin_amdgcn_readlane(g_incl, kWave - 1);
+    const int total = n13_all + __builtin_amdgcn_readlane(c_incl, kWave - 1);
     int at = 0;
     if (lane == 0 && total > 0) at = atomicAdd(&sm.ncand, total);
     at = __builtin_amdgcn_readfirstlane(at);
-    {
+    // The counts cannot exceed the room they index (at most k keys reach tau, a row adds one more
+    // only if none of its keys does, the host sized `cand` for every source) as long as the row
+    // lists are what the stream phase writes: decreasing, distinct keys.  A wave that finds
+    // otherwise writes nothing: a damaged list costs a wrong beam, not a stray write.
+    const int n13 = n13_all <= kStrip ? n13_all : 0;
+    const bool fits = n13_all <= kStrip && at + total <= p.cand_cap;
+    if (n13_all <= kStrip) {
         int to = g_incl - g;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i)
@@ -996,7 +1007,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         int h = 0, w = -1;
         if (valid) {
             const uint32_t code = flatmask - ((uint32_t)body & flatmask);
-            h = (int)(code >> p.tok_bits);
+            h = min((int)(code >> p.tok_bits), kMaxBeam - 1);
             w = (int)(code & tokmask);
         }
         const HypState hs = sm.hyp[h];
@@ -1006,11 +1017,11 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             if (!(hs.misc & kFinFinished))
                 bank = nmet_after(bank, hs.ipq < 0 ? -1 : (hs.ipq >> 8), hs.ipq < 0 ? 0 : (hs.ipq & 255),
                                   w == hs.nxt, match, hs.inc);
-            cand[at + idx] = mb ? (body | ((u64)bank << sel_shift)) : body;
+            if (fits) cand[at + idx] = mb ? (body | ((u64)bank << sel_shift)) : body;
             atomicAdd(&sm.cnt[bank], 1);                  // bank = constraints met (Sec. 3.1)
         }
     }
-    {
+    if (fits) {
         int to = at + n13 + c_incl - c;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
@@ -1021,7 +1032,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         }
     }
     __syncthreads();
-    const int ncand = sm.ncand;
+    const int ncand = min(sm.ncand, p.cand_cap);
     const int nchunks = (ncand + kWave - 1) >> 6;
 
     // ---- slots per bank (Sec. 3.2) --------------------------------------------------------
@@ -1082,13 +1093,16 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         if (mine != 0) {
             const int bank = mb ? (int)(mine >> sel_shift) : 0;
             // within a bank the best alloc[bank] are taken (Sec. 3.1/3.2)
-            if (rank - sm.start[bank] < sm.alloc[bank]) sm.sel[atomicAdd(&sm.nsel, 1)] = mine & body_mask;
+            if (rank - sm.start[bank] < sm.alloc[bank]) {
+                const int place = atomicAdd(&sm.nsel, 1);
+                if (place < kMaxBeam) sm.sel[place] = mine & body_mask;
+            }
         }
     }
     __syncthreads();
 
     // ---- new beam, best first (Sec. 3.1); empty slots last ---------------------------------
-    const int nsel = sm.nsel;
+    const int nsel = min(sm.nsel, k);
     if (wave == 0) {
         // one lane per selected candidate; its place in the new beam is the number of selected
         // keys greater than its own (at most 64 uniform LDS reads: cheaper than a 64-lane sort)
@@ -1110,7 +1124,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
         }
         const u64 match = first_token_matches(live ? token : -1, sm);
         if (live) {
-            const HypState hs = sm.hyp[parent];
+            const HypState hs = sm.hyp[min(parent, kMaxBeam - 1)];
             met2 = hs.met;
             inc2 = hs.inc;
             const int ipq = hs.ipq;
