@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per step (fetched + written by its two launches) on the config-4 workload, from the
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled against a plain copy);
 # None whenever a kernel has changed since those counters were taken.
-TRAFFIC_BYTES_PER_LAUNCH = 168334970
+TRAFFIC_BYTES_PER_LAUNCH = 168341936
 
 
 def build_workload(cfg: int, cons_tokens):
