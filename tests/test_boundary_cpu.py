@@ -81,3 +81,17 @@ def test_null_ctx_calls_fail_cleanly():
     assert lib.dba_steps_done(None) == dba.DBA_EINVAL
     lib.dba_destroy(None)
     assert isinstance(dba.dba_last_error(None), str)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asked for more it says so and exits (before touching any GPU)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for extra_env, argv in (({}, ["--gpus", "2"]), ({"WORLD_SIZE": "4"}, [])):
+        env = dict(os.environ, **extra_env)
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py")] + argv, capture_output=True, text=True,
+                           env=env, timeout=120)
+        assert r.returncode != 0
+        assert "ONE GPU" in r.stderr
+        assert r.stdout.strip() == ""
