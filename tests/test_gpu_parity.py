@@ -294,6 +294,18 @@ def test_paper_setup_config2(torch_gpu):
     _harness().run_parity(wl, normalize=True, prune=20.0)
 
 
+@pytest.mark.parametrize("fmt", [None, "bf16"])
+def test_paper_setup_config4(torch_gpu, fmt):
+    """The headline shape (64 sentences, k = 20, V = 32000, 32 constraint tokens) with the decoding
+    set-up of Sec. 4 - score per word for completed hypotheses, pruning threshold 20 - and
+    end-of-sentence likely from step 12 on, so that hypotheses complete, beams shrink and the
+    stopping test fires at full width; once on fp32 and once on bfloat16 log-probs."""
+    wl = si.make_config(4, T=30)
+    wl.eos_switch = 12
+    _harness().run_parity(wl, normalize=True, prune=20.0, check_state_every=3, logp_format=fmt,
+                          progress="config4/Sec.4")
+
+
 def test_gbs_simulation(torch_gpu):
     """Sec. 5: beam b(C+1), adjustment off - C = 3 single-token constraints, b = 5."""
     B, V, T, b, C = 6, 8000, 25, 5, 3
