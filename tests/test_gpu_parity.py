@@ -306,6 +306,18 @@ def test_paper_setup_config4(torch_gpu, fmt):
                           progress="config4/Sec.4")
 
 
+def test_paper_setup_config5(torch_gpu):
+    """The largest shape (B=128, k=64, V=50000) with the set-up of Sec. 4 and without the adjustment
+    of Sec. 3.2 for a change; end-of-sentence likely from step 5 on.  The oracle follows a sample of
+    sentences, all are checked against the properties that hold at any size."""
+    wl = si.make_config(5, T=12)
+    wl.eos_switch = 5
+    ntok = [wl.n_tokens(b) for b in range(wl.B)]
+    sample = sorted({int(np.argmin(ntok)), int(np.argmax(ntok)), 7, 100})
+    _harness().run_parity(wl, oracle_sentences=sample, normalize=True, prune=20.0, adjust=False,
+                          check_state_every=3, progress="config5/Sec.4")
+
+
 def test_gbs_simulation(torch_gpu):
     """Sec. 5: beam b(C+1), adjustment off - C = 3 single-token constraints, b = 5."""
     B, V, T, b, C = 6, 8000, 25, 5, 3
