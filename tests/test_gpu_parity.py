@@ -256,6 +256,14 @@ def test_one_launch_form_small(torch_gpu, seed):
     _harness().run_parity(wl, options={DBA_OPT_FUSED_LAUNCH: 1})
 
 
+def test_one_launch_form_config4(torch_gpu):
+    """The one-launch form at the headline shape: 1280 workgroups stream, 64 of them go on to merge
+    while others still stream (arrival counters, device-scope hand-over, wave priorities)."""
+    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
+    _harness().run_parity(si.make_config(4, T=16), options={DBA_OPT_FUSED_LAUNCH: 1}, check_state_every=4,
+                          progress="config4/one launch")
+
+
 def test_one_launch_form_config2(torch_gpu):
     from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
     _harness().run_parity(si.make_config(2, T=15), options={DBA_OPT_FUSED_LAUNCH: 1})
