@@ -395,6 +395,42 @@ def test_small_batches_long_rows(torch_gpu, B, k, V, fmt):
     _harness().run_parity(wl, logp_format=fmt)
 
 
+def test_two_contexts_on_their_own_streams(torch_gpu):
+    """Two decodes at once, each context on a stream of its own (default priority), steps enqueued in
+    turn without waiting: all work of a context goes to its stream and contexts share nothing."""
+    from paper_1804_06609_amd.session import Session
+    torch = torch_gpu
+    wls = [si.make_small(9901, 3, 13, 2050, 10, max_phrases=4, max_len=3, dup_prob=0.3),
+           si.make_small(9902, 2, 20, 4099, 10, max_phrases=5, max_len=2, dup_prob=0.2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    sess, beams = [], []
+    for wl, st in zip(wls, streams):
+        wl.eos_switch = 5
+        toks, poff, soff = wl.csr()
+        sess.append(Session(wl.B, wl.k, wl.V, wl.T, wl.eos_id, wl.pad_id, toks, poff, soff, stream=st))
+        beams.append(oracle.BatchBeam(wl.k, wl.V, wl.constraints, wl.eos_id, wl.pad_id))
+    torch.cuda.synchronize()
+    for t in range(10):
+        keep = []
+        for wl, st, ses in zip(wls, streams, sess):
+            with torch.cuda.stream(st):
+                d = torch.from_numpy(wl.logp(t)).cuda()
+                ses.step(d)
+            keep.append(d)
+        for wl, ses, bm in zip(wls, sess, beams):
+            bm.step(wl.logp(t))
+            tok, bp, sc, fl = ses.outputs()
+            assert tok.tobytes() == bm.stacked("token").tobytes(), t
+            assert bp.tobytes() == bm.stacked("backptr").tobytes(), t
+            assert sc.tobytes() == bm.stacked("score").tobytes(), t
+            assert fl.tobytes() == bm.stacked("flags").tobytes(), t
+    for wl, ses, bm in zip(wls, sess, beams):
+        got, want = ses.finalize(), bm.finalize(10)
+        for g, w in zip(got, want):
+            assert np.asarray(g).tobytes() == np.asarray(w).tobytes()
+        ses.close()
+
+
 def test_plain_c_caller(torch_gpu, tmp_path):
     """examples/decode_from_file.c (built with gcc, no binding in between) against the oracle."""
     import os
