@@ -262,10 +262,19 @@ def main():
                 g_bp.tobytes() == ob.stacked("backptr").tobytes() and
                 g_sc.tobytes() == ob.stacked("score").tobytes())
         ses.close()
+        # the same oracle on one core, on a shorter sample (a step there takes about 0.4 s at config 4)
+        S1 = 4 if args.config == 4 else 1
+        ob1 = oracle.BatchBeam(k, V, wl.constraints, wl.eos_id, wl.pad_id)
+        t0 = time.perf_counter()
+        for t in range(S1):
+            ob1.step(host[t % R], threads=1)
+        cpu1_s = time.perf_counter() - t0
         out["cpu_baseline"] = {
             "value": S / cpu_s, "unit": "steps/s", "cores": threads, "kind": "oracle",
             "sample": f"first {S} steps of the same workload, all {B} sentences, one sentence per thread",
             "gpu_matches_oracle_on_sample": bool(same),
+            "one_core": {"value": S1 / cpu1_s, "unit": "steps/s", "cores": 1,
+                         "sample": f"first {S1} steps of the same workload, all {B} sentences"},
         }
     print(json.dumps(out))
 
