@@ -125,7 +125,7 @@ def main():
                          "that a counter run can scale FETCH_SIZE / WRITE_SIZE against it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; sentences shard across GPUs without any "
+        print("bench.py: this library runs on ONE GPU; sentences shard across GPUs without any "
               "exchange, so a multi-GPU figure would be N independent copies of this run. "
               "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
