@@ -183,6 +183,32 @@ def test_ties_fuzz(torch_gpu, seed):
     _harness().run_parity(wl, logp_format=[None, None, "bf16", "f16"][rs.randint(0, 3)])
 
 
+class _ContestedLastPlaces(si.Workload):
+    """Step 0 gives all k hypotheses one score; at step 1 hypothesis 0 has k tokens at one level and
+    hypothesis 8 - same wave, same chain of merges in the merge phase - a single token at that level:
+    k+1 sums tie for the k places, and the list of hypothesis 8 has a head that only equals, never
+    beats, the k-th best found before it.  Later steps are the generator's."""
+
+    def logp(self, t, sentences=None, out=None):
+        lp = super().logp(t, sentences, out)
+        if t == 0:
+            lp[...] = np.float32(-2.0)
+            lp[..., self.eos_id] = np.float32(-60.0)
+        elif t == 1:
+            lp[...] = np.float32(-30.0)
+            lp[:, 0, 100:100 + self.k] = np.float32(-1.0)
+            lp[:, 8, 7] = np.float32(-1.0)
+            lp[:, 3, 50:60] = np.float32(-1.5)
+        return lp
+
+
+@pytest.mark.parametrize("k", [40, 64, 20])
+def test_contested_last_places(torch_gpu, k):
+    wl = _ContestedLastPlaces(B=2, k=k, V=3000, T=4, seed=77, constraints=[[], [[9, 10], [700]]])
+    wl.eos_switch = 1 << 30
+    _harness().run_parity(wl)
+
+
 class _Masked(si.Workload):
     """A decoder with a restricted vocabulary: all but a few entries of every row are -inf (a
     different few in every row and step), so a sentence can have fewer than k finite sums, beams
