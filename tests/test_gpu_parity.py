@@ -209,6 +209,34 @@ def test_contested_last_places(torch_gpu, k):
     _harness().run_parity(wl)
 
 
+class _TiedConstraintToken(si.Workload):
+    """k = 64.  At step 1 hypothesis 0 has 65 tokens at one level: 64 ordinary ones with the lowest ids,
+    which are the sentence's k best and fill the row's list, and the constraint token 500, which has the
+    k-th best score too but is not among the k best nor in the list - it has to come in as a constraint
+    candidate all the same (Sec. 3.1 item 2)."""
+
+    def logp(self, t, sentences=None, out=None):
+        lp = super().logp(t, sentences, out)
+        if t == 0:
+            lp[...] = np.float32(-2.0)
+            lp[..., self.eos_id] = np.float32(-60.0)
+        elif t == 1:
+            lp[...] = np.float32(-30.0)
+            lp[:, 0, 100:164] = np.float32(-1.0)
+            lp[:, 0, 500] = np.float32(-1.0)
+        return lp
+
+
+def test_constraint_token_tied_with_the_k_best_but_not_one_of_them(torch_gpu):
+    wl = _TiedConstraintToken(B=2, k=64, V=3000, T=4, seed=78, constraints=[[[500]], [[500, 9], [700]]])
+    wl.eos_switch = 1 << 30
+    _harness().run_parity(wl)
+    ob = oracle.BatchBeam(wl.k, wl.V, wl.constraints, wl.eos_id, wl.pad_id)
+    for t in range(2):
+        ob.step(wl.logp(t))
+    assert 500 in ob.stacked("token")[0].tolist()      # the case is what it claims to be
+
+
 class _Masked(si.Workload):
     """A decoder with a restricted vocabulary: all but a few entries of every row are -inf (a
     different few in every row and step), so a sentence can have fewer than k finite sums, beams
