@@ -53,6 +53,10 @@ def _load():
                                                                         ctypes.c_float, _P]
         lib.dba_oracle_finalize.restype = ctypes.c_int
         lib.dba_oracle_finalize.argtypes = [ctypes.c_int] * 4 + [_P] * 10 + [ctypes.c_int]
+        lib.dba_oracle_track_completed.restype = None
+        lib.dba_oracle_track_completed.argtypes = [ctypes.c_int, ctypes.c_int, _P, _P, _P, ctypes.c_int, _P, _P]
+        lib.dba_oracle_finalize_tracked.restype = ctypes.c_int
+        lib.dba_oracle_finalize_tracked.argtypes = [ctypes.c_int] * 4 + [_P] * 10 + [ctypes.c_int, _P, _P]
         _lib = lib
     return _lib
 
@@ -109,9 +113,14 @@ class SentenceBeam:
     """Beam of one sentence, advanced by dba_oracle_step."""
 
     def __init__(self, k: int, V: int, phrases, eos_id: int, pad_id: int, adjust: bool = True,
-                 normalize_finished: bool = False, prune_threshold: Optional[float] = None):
+                 normalize_finished: bool = False, prune_threshold: Optional[float] = None,
+                 track_completed: bool = False):
         self.k, self.V, self.eos_id, self.pad_id = k, V, eos_id, pad_id
         self.adjust, self.normalize_finished = bool(adjust), bool(normalize_finished)
+        # variant: remember the best completed hypothesis seen on any beam (Sec. 3.3)
+        self.track_completed = bool(track_completed)
+        self.rec_int = np.zeros(4, dtype=np.int32)      # have, step, slot, length
+        self.rec_flt = np.zeros(2, dtype=np.float32)    # value per word, stored score
         self.prune_threshold = -1.0 if prune_threshold is None else float(prune_threshold)
         self.all_finished = 0
         self.any_finished = 0
@@ -177,6 +186,9 @@ class SentenceBeam:
         self.met, self.ip, self.iq, self.len = o_met, o_ip, o_iq, o_len
         self.hist_token.append(o_tok)
         self.hist_backptr.append(o_bp)
+        if self.track_completed:
+            _load().dba_oracle_track_completed(k, len(self.hist_token) - 1, _ptr(o_sc), _ptr(o_fl), _ptr(o_len),
+                                               int(self.normalize_finished), _ptr(self.rec_int), _ptr(self.rec_flt))
         if debug:
             n = int(d_n[0])
             self.dbg = dict(flat=d_flat[:n].copy(), bank=d_bank[:n].copy(), cnt=d_cnt, alloc=d_alloc)
@@ -191,9 +203,15 @@ class SentenceBeam:
         sc = np.zeros(1, np.float32)
         stt = np.zeros(1, np.int32)
         nm = self.nmet
-        _load().dba_oracle_finalize(self.k, T, N, self.pad_id, _ptr(ht), _ptr(hb), _ptr(self.score),
-                                    _ptr(self.flags), _ptr(self.len), _ptr(nm), _ptr(toks),
-                                    _ptr(ln), _ptr(sc), _ptr(stt), int(self.normalize_finished))
+        if self.track_completed:
+            _load().dba_oracle_finalize_tracked(self.k, T, N, self.pad_id, _ptr(ht), _ptr(hb), _ptr(self.score),
+                                                _ptr(self.flags), _ptr(self.len), _ptr(nm), _ptr(toks),
+                                                _ptr(ln), _ptr(sc), _ptr(stt), int(self.normalize_finished),
+                                                _ptr(self.rec_int), _ptr(self.rec_flt))
+        else:
+            _load().dba_oracle_finalize(self.k, T, N, self.pad_id, _ptr(ht), _ptr(hb), _ptr(self.score),
+                                        _ptr(self.flags), _ptr(self.len), _ptr(nm), _ptr(toks),
+                                        _ptr(ln), _ptr(sc), _ptr(stt), int(self.normalize_finished))
         return toks, int(ln[0]), np.float32(sc[0]), int(stt[0])
 
 

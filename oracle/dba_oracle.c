@@ -47,6 +47,19 @@
  * readings: raw sums decide the selection inside the step in which a
  * hypothesis completes; the pruning cut-off is the fp32 difference best -
  * threshold and a score equal to it survives.
+ *
+ * Completed hypotheses that leave the beam (Sec. 3.3: the highest-scoring
+ * completed item is returned).  A completed hypothesis sits in the topmost
+ * bank and can lose its slot there to candidates with higher sums.  Reading
+ * of the bare algorithm (dba_oracle_finalize): only the final beam is
+ * searched, so such a hypothesis is forgotten.  Variant
+ * (dba_oracle_track_completed + dba_oracle_finalize_tracked): a record of the
+ * best completed hypothesis seen on any beam is kept from step to step and
+ * returned at the end.  Pinned by tests: the returned hypothesis scores at
+ * least as well as every completed hypothesis that ever sat on a beam, found
+ * by walking the recorded beams, and its tokens are the back-trace from the
+ * step and slot where it was seen; with no drop-out both readings agree.
+ * Unpinned: among equal scores the earliest step, then the lowest slot wins.
  */
 #include <math.h>
 #include <stdint.h>
@@ -552,6 +565,64 @@ int dba_oracle_finalize(int k, int T, int N, int pad_id, const int32_t *hist_tok
     int slot = best;
     for (int t = T - 1; t >= 0; --t) {
         if (t < len[best] && t < N) out_tokens[t] = hist_token[(size_t)t * k + slot];
+        slot = hist_backptr[(size_t)t * k + slot];
+    }
+    return 0;
+}
+
+
+/*
+ * Record of the best completed hypothesis seen so far (variant; see the header).
+ * Called after every step with the new beam (after pruning, if any) of step t
+ * (0-based).  A completed hypothesis is ranked by its score per word (Sec. 4):
+ * the stored score itself when the beam already holds sum/length
+ * (scores_normalized), else one fp32 division of the stored sum by the length.
+ * The record changes only for a strictly better value, so a hypothesis that
+ * is carried along on the beam is recorded where it first appeared, and among
+ * equal values the earliest step and then the lowest slot win.
+ * rec_int = {have, step, slot, length}, rec_flt = {value per word, stored score}.
+ */
+void dba_oracle_track_completed(int k, int t, const float *score, const uint8_t *flags,
+                                const int32_t *len, int scores_normalized, int32_t *rec_int,
+                                float *rec_flt)
+{
+    for (int h = 0; h < k; ++h) {
+        if ((flags[h] & FLAG_DEAD) || !(flags[h] & FLAG_FINISHED)) continue;
+        const float q = scores_normalized ? score[h] : score[h] / (float)len[h];
+        if (!rec_int[0] || q > rec_flt[0]) {
+            rec_int[0] = 1;
+            rec_int[1] = t;
+            rec_int[2] = h;
+            rec_int[3] = len[h];
+            rec_flt[0] = q;
+            rec_flt[1] = score[h];
+        }
+    }
+}
+
+/*
+ * End of decoding with the record above: the recorded hypothesis is returned
+ * (status 1; length and score as stored when it was seen; tokens by following
+ * the back-pointers from its step and slot).  Without a record nothing was
+ * ever completed and the fallback of dba_oracle_finalize applies.
+ */
+int dba_oracle_finalize_tracked(int k, int T, int N, int pad_id, const int32_t *hist_token,
+                                const int32_t *hist_backptr, const float *score,
+                                const uint8_t *flags, const int32_t *len, const int32_t *nmet,
+                                int32_t *out_tokens, int32_t *out_len, float *out_score,
+                                int32_t *out_status, int scores_normalized, const int32_t *rec_int,
+                                const float *rec_flt)
+{
+    if (!rec_int[0] || T < 1)
+        return dba_oracle_finalize(k, T, N, pad_id, hist_token, hist_backptr, score, flags, len, nmet,
+                                   out_tokens, out_len, out_score, out_status, scores_normalized);
+    for (int i = 0; i < N; ++i) out_tokens[i] = pad_id;
+    *out_status = 1;
+    *out_len = rec_int[3];
+    *out_score = rec_flt[1];
+    int slot = rec_int[2];
+    for (int t = rec_int[1]; t >= 0; --t) {
+        if (t < rec_int[3] && t < N) out_tokens[t] = hist_token[(size_t)t * k + slot];
         slot = hist_backptr[(size_t)t * k + slot];
     }
     return 0;

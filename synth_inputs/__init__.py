@@ -321,3 +321,32 @@ def make_small(seed: int, B: int, k: int, V: int, T: int, max_phrases: int = 3,
         boosts.append(sorted(set(pool)) if boost else [])
     return Workload(B=B, k=k, V=V, T=T, seed=seed, constraints=cons, zipf_s=zipf_s,
                     boost_tokens=boosts, boost_value=4.0, boost_prob=0.35, name="small")
+
+
+def two_profile_logp(seed: int, t: int, B: int, k: int, V: int, eos_id: int = EOS_ID) -> np.ndarray:
+    """Log-probs [B, k, V] for decodes in which completed hypotheses get onto the beam and are pushed
+    off it again: every row's distribution is one of two profiles over a seeded shuffle of the
+    vocabulary - "peaky" (0.85, 0.10, then a thin tail; end-of-sentence often holds the 0.10) or "flat"
+    (0.46, 0.44, thin tail).  A weak completion enters behind a peaky row's favourite and loses its
+    slot when the survivors' next rows are flat.  log() of the table in double, rounded once to fp32."""
+    assert V >= 6
+    out = np.empty((B, k, V), dtype=np.float32)
+    tail = V - 2
+    for b in range(B):
+        for h in range(k):
+            rs = Stream(seed, (t * B + b) * 64 + h + 90000)
+            peaky = rs.randint(0, 2) != 0
+            top = (0.85, 0.10) if peaky else (0.46, 0.44)
+            rest = (1.0 - top[0] - top[1]) / tail
+            order = list(range(V))
+            for i in range(V - 1, 0, -1):
+                j = rs.randint(0, i)
+                order[i], order[j] = order[j], order[i]
+            if peaky and rs.randint(0, 1) == 0:          # end-of-sentence takes the second place
+                order.remove(eos_id)
+                order.insert(1, eos_id)
+            p = np.empty(V, dtype=np.float64)
+            for place, w in enumerate(order):
+                p[w] = top[place] if place < 2 else rest * (1.0 + 0.01 * place)
+            out[b, h] = np.log(p / p.sum()).astype(np.float32)
+    return out

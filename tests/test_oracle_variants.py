@@ -275,3 +275,100 @@ def test_narrowing_rounds_to_the_nearest_value_ties_to_even(fmt, ebits, mbits):
         if len(ties) == 2:                       # exact tie: the one with an even last bit
             b = int(si.narrow16(np.array([xi], np.float32), fmt)[0])
             assert b & 1 == 0
+
+
+# ---- Sec. 3.3: the best completed hypothesis, also when it has left the beam ---------------------
+def _walk_completed(scores, flags, lens, normalize):
+    """Every completed hypothesis on every recorded beam: (value per word, step, slot)."""
+    seen = []
+    for t in range(len(scores)):
+        for h in range(len(scores[t])):
+            if flags[t][h] == oracle.FLAG_DEAD or not (flags[t][h] & oracle.FLAG_FINISHED):
+                continue
+            q = np.float32(scores[t][h]) if normalize else np.float32(scores[t][h]) / np.float32(lens[t][h])
+            seen.append((q, t, h))
+    return seen
+
+
+def test_tracked_finalize_hand_worked_drop_out():
+    """k = 2, no constraints, ids: 0 pad, 2 end-of-sentence.  Step 0: the beam becomes [3 (-0.1),
+    end-of-sentence (-3.0, completed, one word)].  Step 1: both continuations of 3 (-0.6, -1.1) beat
+    the completed hypothesis, which leaves the beam.  Step 2: one of them completes at -10.6 over
+    three words = -3.53 per word, worse than -3.0 per word.  The bare reading returns the three-word
+    hypothesis (the only completed one on the last beam); the tracking variant returns the one-word
+    hypothesis seen at step 0."""
+    V, k, T, lo = 6, 2, 3, np.float32(-50.0)
+    lp = np.full((T, k, V), lo, np.float32)
+    lp[0, 0, 3], lp[0, 0, 2] = -0.1, -3.0
+    lp[1, 0, 4], lp[1, 0, 5] = -0.5, -1.0
+    lp[2, 0, 2], lp[2, 0, 3] = -10.0, -20.0
+    lp[2, 1, 3] = -0.3
+    res = {}
+    for track in (False, True):
+        bm = oracle.SentenceBeam(k, V, [], 2, 0, track_completed=track)
+        for t in range(T):
+            bm.step(lp[t])
+            if t == 0:
+                assert list(bm.token) == [3, 2] and list(bm.flags) == [0, 1]
+            if t == 1:
+                assert list(bm.token) == [4, 5] and list(bm.flags) == [0, 0]
+        assert list(bm.token) == [3, 2] and list(bm.backptr) == [1, 0] and list(bm.flags) == [0, 1]
+        res[track] = bm.finalize(4)
+    toks, ln, sc, status = res[False]
+    assert status == 1 and ln == 3 and list(toks) == [3, 4, 2, 0] and sc == np.float32(np.float32(-0.1) + np.float32(-0.5)) + np.float32(-10.0)
+    toks, ln, sc, status = res[True]
+    assert status == 1 and ln == 1 and list(toks) == [2, 0, 0, 0] and sc == np.float32(-3.0)
+
+
+def test_tracked_finalize_returns_the_best_completed_hypothesis_ever_seen():
+    """The variant that remembers completed hypotheses, on decodes in which completed hypotheses
+    get onto the beam and are pushed off again: what the end of decoding returns scores at least as
+    well, per word, as every completed hypothesis that sat on any beam (walked here from the recorded
+    beams; its value recomputed from the log-probs along its back-pointers), its tokens are the
+    back-trace from where it was first seen, and where it is still on the last beam, alone with its
+    value, the bare reading returns the same."""
+    dropped = agree = 0
+    for seed in range(400):
+        normalize = bool(seed & 1)
+        k, V, T = [2, 3, 4, 5][seed % 4], 8, 12
+        cons = [[], [[5]], [[4, 6]], [[3], [7]]][(seed // 4) % 4]
+        eos, pad = 2, 0
+        bm = oracle.SentenceBeam(k, V, cons, eos, pad, track_completed=True, normalize_finished=normalize)
+        plain = oracle.SentenceBeam(k, V, cons, eos, pad, normalize_finished=normalize)
+        logps, scores, flags, lens = [], [], [], []
+        for t in range(T):
+            logps.append(si.two_profile_logp(700 + seed, t, 1, k, V)[0])
+            bm.step(logps[-1])
+            plain.step(logps[-1])
+            assert bm.score.tobytes() == plain.score.tobytes() and bm.token.tobytes() == plain.token.tobytes()
+            scores.append(bm.score.copy())
+            flags.append(bm.flags.copy())
+            lens.append(bm.len.copy())
+        toks, ln, sc, status = bm.finalize(T)
+        p_toks, p_ln, p_sc, p_status = plain.finalize(T)
+        seen = _walk_completed(scores, flags, lens, normalize)
+        if not seen:
+            assert status == 0 and p_status == 0
+            assert toks.tobytes() == p_toks.tobytes() and (ln, sc) == (p_ln, p_sc)
+            continue
+        best_q = max(q for q, _, _ in seen)
+        t0, h0 = min((t, h) for q, t, h in seen if q == best_q)
+        assert status == 1 and ln == lens[t0][h0] and sc == scores[t0][h0]
+        # its tokens: back-pointers from (t0, h0); its value: the log-probs along that path
+        want, slot = [], h0
+        for u in range(t0, -1, -1):
+            want.append(int(bm.hist_token[u][slot]))
+            slot = int(bm.hist_backptr[u][slot])
+        want = want[::-1][:ln]
+        assert list(toks[:ln]) == want and want[-1] == eos and (toks[ln:] == pad).all()
+        s, n = _path_sum(logps, bm.hist_token, bm.hist_backptr, t0, h0, eos)
+        assert n == ln and best_q == np.float32(s) / np.float32(n)
+        last_vals = [q for q, _, _ in _walk_completed([scores[-1]], [flags[-1]], [lens[-1]], normalize)]
+        if best_q not in last_vals:
+            # it has left the beam: the bare reading returns something worse per word, or nothing
+            dropped += 1
+            assert p_status == 0 or (p_sc if normalize else np.float32(p_sc) / np.float32(p_ln)) < best_q
+        elif last_vals.count(best_q) == 1 and len({(t, h) for q, t, h in seen if q == best_q and t == t0}) == 1:
+            assert p_status == 1 and (p_ln, p_sc) == (ln, sc) and p_toks.tobytes() == toks.tobytes()
+            agree += 1
+    assert dropped >= 10 and agree >= 100, (dropped, agree)
