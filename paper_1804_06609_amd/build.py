@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdba.so")
 SOURCES = [os.path.join(CSRC, "dba.hip")]
 DEPS = SOURCES + [os.path.join(CSRC, f) for f in ("dba_kernels.hpp", "wave_topk.hpp")] + [
-    os.path.join(os.path.dirname(HERE), "include", "dba.h")]
+    os.path.join(os.path.dirname(HERE), "include", f) for f in ("dba.h", "dba_debug.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

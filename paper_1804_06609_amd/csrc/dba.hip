@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "../../include/dba.h"
+#include "../../include/dba_debug.h"
 #include "dba_kernels.hpp"
 
 using namespace dba;
@@ -239,7 +240,8 @@ __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float
 // decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0
 __global__ void dba_init_state_kernel(int B, int k, const int32_t *phr_off, const int32_t *nphr, float *score,
                                       u64 *met, int32_t *ipq, int32_t *len, uint8_t *fin, u64 *inc,
-                                      int32_t *nxt, unsigned int *counters, uint8_t *all_finished)
+                                      int32_t *nxt, unsigned int *counters, uint8_t *all_finished,
+                                      BestCompleted *best)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < B * k) {
@@ -257,15 +259,18 @@ __global__ void dba_init_state_kernel(int B, int k, const int32_t *phr_off, cons
     if (i < B) {
         counters[i] = 0;
         all_finished[i] = 0;
+        BestCompleted none = {};
+        best[i] = none;
     }
 }
 
 // End of decoding (Sec. 3.3, length normalisation of Sec. 4): one thread per sentence.
+// best != null: the record of the best completed hypothesis seen on any beam decides, if there is one.
 __global__ void dba_finalize_kernel(int B, int k, int T, int N, int pad_id, int normalized,
                                     const int32_t *hist_token, const int32_t *hist_backptr,
                                     const float *score, const u64 *met, const int32_t *len,
-                                    const uint8_t *fin, int32_t *out_tokens, int32_t *out_len,
-                                    float *out_score, int32_t *out_status)
+                                    const uint8_t *fin, const BestCompleted *best_rec, int32_t *out_tokens,
+                                    int32_t *out_len, float *out_score, int32_t *out_status)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
@@ -275,6 +280,19 @@ __global__ void dba_finalize_kernel(int B, int k, int T, int N, int pad_id, int 
     out_score[b] = -INFINITY;
     out_status[b] = 0;
     if (T < 1) return;
+    if (best_rec && best_rec[b].have) {
+        const BestCompleted r = best_rec[b];
+        out_status[b] = 1;
+        out_len[b] = r.len;
+        out_score[b] = r.score;
+        int slot = r.slot;
+        for (int t = r.step; t >= 0; --t) {
+            const size_t at = ((size_t)t * B + b) * k + slot;
+            if (t < r.len && t < N) toks[t] = hist_token[at];
+            slot = hist_backptr[at];
+        }
+        return;
+    }
     const size_t o = (size_t)b * k;
     int best = -1;
     float bestq = 0.0f;
@@ -341,7 +359,7 @@ struct Layout {
     size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2];
     size_t cons_tok, phr_off, nphr, ftok, sfl, bloom, btok, rowlists, conskeys, counters;
     size_t hist_token, hist_backptr;
-    size_t fin_tokens, fin_len, fin_score, fin_status, all_finished;
+    size_t fin_tokens, fin_len, fin_score, fin_status, all_finished, best;
     size_t total;
 };
 
@@ -380,6 +398,7 @@ Layout make_layout(size_t B, size_t k, size_t N)
     L.fin_score = take(B * sizeof(float));
     L.fin_status = take(B * sizeof(int32_t));
     L.all_finished = take(B);
+    L.best = take(B * sizeof(BestCompleted));
     L.total = off;
     return L;
 }
@@ -403,6 +422,7 @@ struct dba_ctx {
     int adjust;                         // DBA_OPT_ADJUSTMENT
     int normalize;                      // DBA_OPT_NORMALIZE_FINISHED
     float prune;                        // DBA_OPT_PRUNE_THRESHOLD (< 0: off)
+    int track;                          // DBA_OPT_TRACK_COMPLETED
     size_t dyn_smem;
     unsigned char *ws;
     Layout L;
@@ -462,10 +482,11 @@ DBA_API size_t dba_workspace_bytes(int B, int k, int V, int N, int max_cons_toke
     return make_layout((size_t)B, (size_t)k, (size_t)N).total;
 }
 
-DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int pad_id,
-             const int32_t *cons_tokens, const int32_t *phrase_offsets,
-             const int32_t *sent_offsets, void *workspace_dev, size_t workspace_bytes,
-             void *hip_stream)
+// dba_init proper; may throw std::bad_alloc from its host tables (caught by dba_init)
+static int init_impl(dba_ctx **out, int B, int k, int V, int N, int eos_id, int pad_id,
+                     const int32_t *cons_tokens, const int32_t *phrase_offsets,
+                     const int32_t *sent_offsets, void *workspace_dev, size_t workspace_bytes,
+                     void *hip_stream)
 {
     if (!out) return fail(nullptr, DBA_EINVAL, "dba_init: out is NULL");
     *out = nullptr;
@@ -562,6 +583,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->adjust = 1;
     c->normalize = 0;
     c->prune = -1.0f;
+    c->track = 0;
     // candidates of one sentence: at most k best + k row bests + k * phrases constraint tokens,
     // in whole chunks of 64 keys (at most 4224 keys = 33 KB of LDS)
     const int ncand_max = (k * (max_phrases + 2) + kWave - 1) / kWave * kWave;
@@ -587,7 +609,7 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
             B, k, at<int32_t>(c, L.phr_off), at<int32_t>(c, L.nphr), at<float>(c, L.score[0]),
             at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]), at<int32_t>(c, L.len[0]),
             at<uint8_t>(c, L.fin[0]), at<u64>(c, L.inc[0]), at<int32_t>(c, L.nxt[0]),
-            at<unsigned int>(c, L.counters), at<uint8_t>(c, L.all_finished));
+            at<unsigned int>(c, L.counters), at<uint8_t>(c, L.all_finished), at<BestCompleted>(c, L.best));
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);   // host tables are freed on return
@@ -600,14 +622,31 @@ DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     return DBA_OK;
 }
 
+DBA_API int dba_init(dba_ctx **out, int B, int k, int V, int N, int eos_id, int pad_id,
+             const int32_t *cons_tokens, const int32_t *phrase_offsets,
+             const int32_t *sent_offsets, void *workspace_dev, size_t workspace_bytes,
+             void *hip_stream)
+{
+    try {
+        return init_impl(out, B, k, V, N, eos_id, pad_id, cons_tokens, phrase_offsets, sent_offsets,
+                         workspace_dev, workspace_bytes, hip_stream);
+    } catch (...) {                                        // nothing crosses the C boundary
+        if (out) *out = nullptr;
+        return fail(nullptr, DBA_ENOMEM, "dba_init: out of host memory");
+    }
+}
+
 DBA_API int dba_step(dba_ctx *c, const float *logp_dev, int32_t *out_token_dev, int32_t *out_backptr_dev,
              float *out_score_dev, uint8_t *out_flags_dev)
 {
     return dba_step_fmt(c, logp_dev, DBA_LOGP_F32, out_token_dev, out_backptr_dev, out_score_dev, out_flags_dev);
 }
 
-DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int32_t *out_token_dev,
-                         int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev)
+// One step.  own_scratch: the row lists and constraint keys go through the library's own scratch
+// (given here as its device address) instead of the workspace.
+static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t *out_token_dev,
+                     int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev,
+                     unsigned char *own_scratch)
 {
     if (!c) return DBA_EINVAL;
     if (!logp_dev) return fail(c, DBA_EINVAL, "dba_step: logp_dev is NULL");
@@ -630,6 +669,8 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
     p.adjust = c->adjust;
     p.normalize = c->normalize;
     p.prune = c->prune;
+    p.track = c->track;
+    p.step = c->steps;
     p.logp = logp_dev;
     p.score_cur = at<float>(c, L.score[cur]);
     p.met_cur = at<u64>(c, L.met[cur]);
@@ -652,8 +693,8 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
     p.same_first_lower = at<u64>(c, L.sfl);
     p.first_bucket = at<u64>(c, L.bloom);
     p.bucket_tok = at<int32_t>(c, L.btok);
-    p.rowlists = at<u64>(c, L.rowlists);
-    p.conskeys = at<u64>(c, L.conskeys);
+    p.rowlists = own_scratch ? reinterpret_cast<u64 *>(own_scratch) : at<u64>(c, L.rowlists);
+    p.conskeys = own_scratch ? reinterpret_cast<u64 *>(own_scratch) + (size_t)c->B * c->k * kWave : at<u64>(c, L.conskeys);
     p.counters = at<unsigned int>(c, L.counters);
     p.out_token = out_token_dev;
     p.out_backptr = out_backptr_dev;
@@ -663,13 +704,14 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
     p.hist_token = at<int32_t>(c, L.hist_token) + hrow;
     p.hist_backptr = at<int32_t>(c, L.hist_backptr) + hrow;
     p.all_finished = at<uint8_t>(c, L.all_finished);
+    p.best = at<BestCompleted>(c, L.best);
 
     // 4 wavefronts per row, 4 loads of 16 bytes per lane and tile: 1280 rows x 4 waves fill the 1024 SIMDs
     // five deep with two 4 KB tiles in flight per wave (measured best on MI355X at V = 32000)
     const dim3 grid((unsigned)(c->B * c->k)), block(kBlock);
     // the merge phase is compiled for 4, 8 and 16 beam rows per wave: the smallest that holds k
     const int rows = c->k <= 16 ? 4 : (c->k <= 32 ? 8 : 16);
-    if (c->fused) {
+    if (c->fused && !own_scratch) {
         launch_fused(logp_format, rows, grid, block, c->dyn_smem, c->stream, p);
     } else {
         switch (logp_format) {
@@ -688,6 +730,13 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
     return DBA_OK;
 }
 
+DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int32_t *out_token_dev,
+                         int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev)
+{
+    return step_impl(c, logp_dev, logp_format, out_token_dev, out_backptr_dev, out_score_dev, out_flags_dev,
+                     nullptr);
+}
+
 DBA_API int dba_finalize(dba_ctx *c, int32_t *out_tokens_host, int32_t *out_len_host, float *out_score_host,
                  int32_t *out_status_host)
 {
@@ -700,7 +749,8 @@ DBA_API int dba_finalize(dba_ctx *c, int32_t *out_tokens_host, int32_t *out_len_
         c->B, c->k, c->steps, c->N, c->pad_id, c->normalize, at<int32_t>(c, L.hist_token),
         at<int32_t>(c, L.hist_backptr),
         at<float>(c, L.score[cur]), at<u64>(c, L.met[cur]), at<int32_t>(c, L.len[cur]),
-        at<uint8_t>(c, L.fin[cur]), at<int32_t>(c, L.fin_tokens), at<int32_t>(c, L.fin_len),
+        at<uint8_t>(c, L.fin[cur]), c->track ? at<BestCompleted>(c, L.best) : nullptr,
+        at<int32_t>(c, L.fin_tokens), at<int32_t>(c, L.fin_len),
         at<float>(c, L.fin_score), at<int32_t>(c, L.fin_status));
     hipError_t e = hipGetLastError();
     const size_t B = (size_t)c->B;
@@ -724,14 +774,21 @@ DBA_API int dba_get_state(dba_ctx *c, float *score_host, uint64_t *met_mask_host
     const Layout &L = c->L;
     const int cur = c->steps & 1;
     const size_t n = (size_t)c->B * c->k;
-    std::vector<float> score(n);
-    std::vector<int32_t> ipq(n);
-    std::vector<uint8_t> fin(n);
-    hipError_t e = hipMemcpyAsync(score.data(), at<float>(c, L.score[cur]), n * 4, hipMemcpyDeviceToHost, c->stream);
+    // one host block for the three arrays this call decodes: n floats, n ints, n bytes
+    unsigned char *tmp = static_cast<unsigned char *>(malloc(n * 9 + 16));
+    if (!tmp) return fail(c, DBA_ENOMEM, "dba_get_state: out of host memory");
+    struct Free {
+        unsigned char *p;
+        ~Free() { free(p); }
+    } guard{tmp};
+    float *score = reinterpret_cast<float *>(tmp);
+    int32_t *ipq = reinterpret_cast<int32_t *>(tmp + n * 4);
+    uint8_t *fin = tmp + n * 8;
+    hipError_t e = hipMemcpyAsync(score, at<float>(c, L.score[cur]), n * 4, hipMemcpyDeviceToHost, c->stream);
     if (e == hipSuccess)
-        e = hipMemcpyAsync(ipq.data(), at<int32_t>(c, L.ipq[cur]), n * 4, hipMemcpyDeviceToHost, c->stream);
+        e = hipMemcpyAsync(ipq, at<int32_t>(c, L.ipq[cur]), n * 4, hipMemcpyDeviceToHost, c->stream);
     if (e == hipSuccess)
-        e = hipMemcpyAsync(fin.data(), at<uint8_t>(c, L.fin[cur]), n, hipMemcpyDeviceToHost, c->stream);
+        e = hipMemcpyAsync(fin, at<uint8_t>(c, L.fin[cur]), n, hipMemcpyDeviceToHost, c->stream);
     if (e == hipSuccess && met_mask_host)
         e = hipMemcpyAsync(met_mask_host, at<u64>(c, L.met[cur]), n * 8, hipMemcpyDeviceToHost, c->stream);
     if (e == hipSuccess && length_host)
@@ -760,6 +817,7 @@ DBA_API int dba_set_option(dba_ctx *c, int option, double value)
         case DBA_OPT_ADJUSTMENT: c->adjust = value != 0.0 ? 1 : 0; return DBA_OK;
         case DBA_OPT_NORMALIZE_FINISHED: c->normalize = value != 0.0 ? 1 : 0; return DBA_OK;
         case DBA_OPT_PRUNE_THRESHOLD: c->prune = value < 0.0 ? -1.0f : (float)value; return DBA_OK;
+        case DBA_OPT_TRACK_COMPLETED: c->track = value != 0.0 ? 1 : 0; return DBA_OK;
         default: return fail(c, DBA_EINVAL, "dba_set_option: unknown option %d", option);
     }
 }

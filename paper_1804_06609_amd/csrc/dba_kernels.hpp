@@ -41,6 +41,8 @@ struct StepParams {
     int adjust;                       // 0: bank sizes stay at the base split (Sec. 5)
     int normalize;                    // 1: a hypothesis completing now is stored with sum / length (Sec. 4)
     float prune;                      // >= 0: threshold pruning against the best completed hypothesis (Sec. 4)
+    int track;                        // 1: keep a record of the best completed hypothesis seen on any beam (Sec. 3.3)
+    int step;                         // index of this step, from 0
     const void *logp;                 // [B,k,V] in the element type the kernel is instantiated for
     // beam before the step
     const float *score_cur;           // [B,k]  (-inf: empty slot)
@@ -78,6 +80,18 @@ struct StepParams {
     int32_t *hist_token, *hist_backptr;   // row t of the history, [B,k]
     uint8_t *all_finished;            // [B] bit 0: the new beam is not empty and every hypothesis on it is completed;
                                       //     bit 1: some hypothesis on it is completed
+    struct BestCompleted *best;       // [B] the record kept under `track`
+};
+
+// The best completed hypothesis a sentence has had on any of its beams so far (Sec. 3.3 returns the
+// highest-scoring completed item; Sec. 4 ranks completed hypotheses by score per word).
+struct __attribute__((aligned(32))) BestCompleted {
+    int have;          // 0: nothing completed yet
+    int step, slot;    // where it was first seen: the beam after step `step`, place `slot`
+    int len;           // its length, end-of-sentence included
+    float q;           // its score per word
+    float score;       // its score as that beam held it
+    int pad[2];
 };
 
 // constraints of one sentence: token ids phrase after phrase, phrase p = tok[poff[p] .. poff[p+1])
@@ -1220,6 +1234,31 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
             if (p.out_flags) p.out_flags[o] = 2;
         }
         const u64 closed = __ballot(keep && fin2);
+        if (p.track && closed != 0) {
+            // Sec. 3.3: a completed hypothesis may lose its slot later on, so the best one seen so
+            // far is remembered: value per word (the stored score where the beam already holds it
+            // per word), replaced only by a strictly better one - the earliest step, then the
+            // lowest slot keep a tie.  A hypothesis carried along compares equal to its own record.
+            const bool cl = keep && fin2;
+            const float q = !cl ? -INFINITY : (p.normalize ? score : __fdiv_rn(score, (float)length));
+            float best = q;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) best = fmaxf(best, __shfl_xor(best, d, kWave));
+            int first = (cl && q == best) ? slot : kWave;
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) first = min(first, __shfl_xor(first, d, kWave));
+            if (cl && slot == first) {
+                BestCompleted *r = p.best + b;
+                if (!r->have || best > r->q) {
+                    r->have = 1;
+                    r->step = p.step;
+                    r->slot = slot;
+                    r->len = length;
+                    r->q = best;
+                    r->score = score;
+                }
+            }
+        }
         if (lane == 0)                                    // stopping tests: Sec. 4 (all), Sec. 6.3 (any)
             p.all_finished[b] = (uint8_t)(((nlive > 0 && open == 0) ? 1 : 0) | (closed != 0 ? 2 : 0));
     }

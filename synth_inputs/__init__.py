@@ -350,3 +350,18 @@ def two_profile_logp(seed: int, t: int, B: int, k: int, V: int, eos_id: int = EO
                 p[w] = top[place] if place < 2 else rest * (1.0 + 0.01 * place)
             out[b, h] = np.log(p / p.sum()).astype(np.float32)
     return out
+
+
+@dataclass
+class TwoProfileWorkload(Workload):
+    """A Workload whose log-probs come from two_profile_logp (V is small: 6..64)."""
+
+    def logp(self, t: int, sentences: Optional[Sequence[int]] = None,
+             out: Optional[np.ndarray] = None) -> np.ndarray:
+        lp = two_profile_logp(self.seed, t, self.B, self.k, self.V, self.eos_id)
+        if sentences is not None:
+            lp = np.ascontiguousarray(lp[list(sentences)])
+        if out is not None:
+            out[...] = lp
+            return out
+        return lp

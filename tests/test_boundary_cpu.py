@@ -1,5 +1,5 @@
 """Host-side checks of the C-ABI library that need no GPU: it loads, exports every
-symbol include/dba.h declares, and rejects bad arguments before touching the device."""
+symbol include/*.h declares, and rejects bad arguments before touching the device."""
 import ctypes
 import os
 import re
@@ -14,16 +14,21 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FAKE_WS = 1 << 20          # an aligned fake device address: argument checks come before any use
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "dba.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"DBA_API\s+[\w\s\*]+?\b(dba_\w+)\s*\(", text)))
+def _declared_symbols(headers=("dba.h", "dba_debug.h")):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"DBA_API\s+[\w\s\*]+?\b(dba_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_boundary():
-    names = _declared_symbols()
+    names = _declared_symbols(("dba.h",))
     for must in ("dba_init", "dba_step", "dba_finalize", "dba_workspace_bytes", "dba_destroy"):
         assert must in names
+    assert not [n for n in names if n.startswith("dba_debug_")]      # diagnostics have a header of their own
+    assert all(n.startswith("dba_debug_") for n in _declared_symbols(("dba_debug.h",)))
 
 
 def test_library_exports_every_declared_symbol():

@@ -370,14 +370,33 @@ def test_paper_setup_config4(torch_gpu, fmt):
 
 def test_paper_setup_config5(torch_gpu):
     """The largest shape (B=128, k=64, V=50000) with the set-up of Sec. 4 and without the adjustment
-    of Sec. 3.2 for a change; end-of-sentence likely from step 5 on.  The oracle follows a sample of
-    sentences, all are checked against the properties that hold at any size."""
+    of Sec. 3.2 for a change; end-of-sentence likely from step 5 on.  The oracle follows all 128
+    sentences through the 12 steps."""
     wl = si.make_config(5, T=12)
     wl.eos_switch = 5
-    ntok = [wl.n_tokens(b) for b in range(wl.B)]
-    sample = sorted({int(np.argmin(ntok)), int(np.argmax(ntok)), 7, 100})
-    _harness().run_parity(wl, oracle_sentences=sample, normalize=True, prune=20.0, adjust=False,
-                          check_state_every=3, progress="config5/Sec.4")
+    _harness().run_parity(wl, normalize=True, prune=20.0, adjust=False, check_state_every=3,
+                          progress="config5/Sec.4")
+
+
+@pytest.mark.parametrize("normalize,prune", [(False, None), (True, None), (False, 20.0), (True, 3.0)])
+def test_completed_hypotheses_that_leave_the_beam(torch_gpu, normalize, prune):
+    """Sec. 3.3 with the record of the best completed hypothesis: 240 short decodes (k = 2..5, with and
+    without constraints) whose log-probs push completed hypotheses off the beam again; the end of
+    decoding must return what the oracle's record returns - and, without per-word scores on the beam,
+    something other than the bare reading for some sentences (the case the record exists for)."""
+    B, V, T = 240, 8, 12
+    shapes = [[], [[5]], [[4, 6]], [[3], [7]]]
+    fins = {}
+    for k in (2, 3, 4, 5):
+        cons = [shapes[(b // 3) % 4] for b in range(B)]
+        wl = si.TwoProfileWorkload(B=B, k=k, V=V, T=T, seed=8100 + k, constraints=cons)
+        wl.eos_switch = 0
+        for track in (True, False):
+            fins[track] = _harness().run_parity(wl, normalize=normalize, prune=prune, track=track,
+                                                check_state_every=4)
+        differ = sum(1 for b in range(B) if fins[True][0][b].tobytes() != fins[False][0][b].tobytes())
+        if not normalize:
+            assert differ >= 2, (k, differ)
 
 
 def test_gbs_simulation(torch_gpu):
@@ -413,10 +432,9 @@ def test_16bit_logp_config2_paper_setup(torch_gpu, fmt):
 
 @pytest.mark.parametrize("fmt", ["f16", "bf16"])
 def test_16bit_logp_config4(torch_gpu, fmt):
-    """The headline shapes with 16-bit log-probs, 12 steps, oracle on 16 sampled sentences."""
+    """The headline shapes with 16-bit log-probs, 12 steps, all 64 sentences against the oracle."""
     wl = si.make_config(4, T=12)
-    _harness().run_parity(wl, logp_format=fmt, oracle_sentences=range(0, 64, 4), check_state_every=4,
-                          progress=f"config4 {fmt}")
+    _harness().run_parity(wl, logp_format=fmt, check_state_every=4, progress=f"config4 {fmt}")
 
 
 def test_16bit_logp_one_launch_form(torch_gpu):
@@ -564,14 +582,19 @@ def test_config4(torch_gpu):
 
 
 def test_config5(torch_gpu):
-    """Full shape (B=128, k=64, V=50000).  The oracle follows a sample of sentences through
-    every step (its cost per sentence-step is ~0.3 s); all sentences are checked against the
-    properties that hold at any size.  DBA_TEST_CONFIG5_STEPS overrides the step count."""
+    """Full shape (B=128, k=64, V=50000), all 120 steps, EVERY sentence: the oracle's cost per sentence
+    and step is ~0.3 s, so it followed all 128 sentences beforehand (tests/golden/make_config5_digests.py,
+    oracle/ only) and left a chained digest of every step's tokens, parents, scores, flags and constraint
+    state per sentence; the GPU outputs of all sentences go through the same chains here and must agree
+    at every stored step and at the end of decoding.  Eight sentences are also followed by the oracle
+    live, element by element, and must reproduce the stored digests themselves.
+    DBA_TEST_CONFIG5_STEPS cuts the run short."""
     T = int(os.environ.get("DBA_TEST_CONFIG5_STEPS", "120"))
     wl = si.make_config(5, T=T)
     ntok = [wl.n_tokens(b) for b in range(wl.B)]
     sample = sorted({int(np.argmin(ntok)), int(np.argmax(ntok)), 0, 1, 63, 64, 126, 127})
-    _harness().run_parity(wl, oracle_sentences=sample, check_state_every=5, progress="config5")
+    golden = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config5_digests.txt")
+    _harness().run_parity(wl, oracle_sentences=sample, check_state_every=5, progress="config5", golden=golden)
 
 
 @pytest.mark.gpu
