@@ -127,6 +127,25 @@ DBA_API int dba_step_fmt(dba_ctx *ctx, const void *logp_dev, int logp_format, in
                          int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev);
 
 /*
+ * dba_step_fmt for callers that must not allocate and want the library to bring its own scratch:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  (No entry
+ * point of this library allocates device memory; here even the scratch that passes a step's
+ * intermediate results - every beam row's list of best sums and its constraint-token keys - from
+ * the first launch to the second is not taken from the caller's workspace but from a fixed array
+ * inside the library, 8 MiB per GPU, resolved once per device.)  Same arguments, same results and
+ * the same asynchronous behaviour as dba_step_fmt; calls may be mixed with dba_step / dba_step_fmt
+ * on the same ctx from step to step.  The step always runs as two launches (DBA_OPT_FUSED_LAUNCH is
+ * ignored).  Nothing in the array has to start at zero: every step overwrites what it reads.
+ * Limits: B*k <= DBA_NOALLOC_MAX_ROWS, else DBA_EINVAL with a message (no launch).  All contexts on
+ * one GPU share that GPU's array: steps of different contexts that overlap in time (different
+ * streams) race on it - keep such steps on one stream or use dba_step.  The device that was current
+ * at dba_init must be current.  Calls no hipMalloc / hipFree.
+ */
+#define DBA_NOALLOC_MAX_ROWS 8192
+DBA_API int dba_step_noalloc(dba_ctx *ctx, const void *logp_dev, int logp_format, int32_t *out_token_dev,
+                             int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev);
+
+/*
  * End of Alg. 1 with Sec. 3.3 and the length normalisation of Sec. 4: for each
  * sentence the completed hypothesis (end-of-sentence generated, hence all
  * constraints met) with the best score/length, traced back through the

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdba.so")
 DBA_OK, DBA_EINVAL, DBA_ESTATE, DBA_EHIP, DBA_ENOMEM = 0, -1, -2, -3, -4
 DBA_FLAG_FINISHED, DBA_FLAG_DEAD = 1, 2
 DBA_MAX_BEAM, DBA_MAX_CONS_TOKENS = 64, 64
+DBA_NOALLOC_MAX_ROWS = 8192
 DBA_LOGP_F32, DBA_LOGP_F16, DBA_LOGP_BF16 = 0, 1, 2
 DBA_STOP_ALL, DBA_STOP_ANY = 1, 2
 DBA_OPT_FUSED_LAUNCH, DBA_OPT_ADJUSTMENT, DBA_OPT_NORMALIZE_FINISHED, DBA_OPT_PRUNE_THRESHOLD = 1, 2, 3, 4
@@ -31,6 +32,7 @@ _SIGNATURES = {
     "dba_init": (_I, [_P] + [_I] * 6 + [_P] * 4 + [ctypes.c_size_t, _P]),
     "dba_step": (_I, [_P] * 6),
     "dba_step_fmt": (_I, [_P, _P, _I] + [_P] * 4),
+    "dba_step_noalloc": (_I, [_P, _P, _I] + [_P] * 4),
     "dba_finalize": (_I, [_P] * 5),
     "dba_get_state": (_I, [_P] * 7),
     "dba_steps_done": (_I, [_P]),
@@ -115,6 +117,13 @@ def dba_step_fmt(ctx, logp_dev: int, logp_format: int, out_token_dev: int = 0, o
     return _check(load().dba_step_fmt(ctx, logp_dev, logp_format, out_token_dev or None,
                                       out_backptr_dev or None, out_score_dev or None,
                                       out_flags_dev or None), ctx)
+
+
+def dba_step_noalloc(ctx, logp_dev: int, logp_format: int, out_token_dev: int = 0, out_backptr_dev: int = 0,
+                     out_score_dev: int = 0, out_flags_dev: int = 0) -> int:
+    return _check(load().dba_step_noalloc(ctx, logp_dev, logp_format, out_token_dev or None,
+                                          out_backptr_dev or None, out_score_dev or None,
+                                          out_flags_dev or None), ctx)
 
 
 def dba_finalize(ctx, out_tokens: np.ndarray, out_len: np.ndarray, out_score: np.ndarray,

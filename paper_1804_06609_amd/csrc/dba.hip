@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -412,6 +413,45 @@ int bits_for(int v)   // bits needed to hold values 0..v
 
 }  // namespace
 
+// ---------------------------------------------------------------------------
+// scratch owned by the library, for dba_step_noalloc
+// ---------------------------------------------------------------------------
+// The two arrays that pass a step's results from its first launch to its second (every row's list
+// and its constraint keys, 64 keys of 8 bytes each) for up to DBA_NOALLOC_MAX_ROWS beam rows: 8 MiB,
+// present once on every GPU the library runs on, until the process ends.
+constexpr size_t kStaticRows = DBA_NOALLOC_MAX_ROWS;
+constexpr size_t kStaticListBytes = kStaticRows * kWave * sizeof(u64);
+constexpr size_t kStaticScratchBytes = kStaticListBytes + kStaticRows * kMaxCons * sizeof(u64);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each GPU (its name is a host-side stand-in)
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device: asked for once per device, kept afterwards.
+hipError_t static_scratch(void **out)
+{
+    *out = nullptr;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
 struct dba_ctx {
     int B, k, V, N, eos_id, pad_id;
     int met_bits;
@@ -423,6 +463,8 @@ struct dba_ctx {
     int normalize;                      // DBA_OPT_NORMALIZE_FINISHED
     float prune;                        // DBA_OPT_PRUNE_THRESHOLD (< 0: off)
     int track;                          // DBA_OPT_TRACK_COMPLETED
+    int device;                         // the device that was current at dba_init
+    unsigned char *lib_scratch;         // this device's copy of the library's own scratch (null: not resolved)
     size_t dyn_smem;
     unsigned char *ws;
     Layout L;
@@ -584,6 +626,11 @@ static int init_impl(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->normalize = 0;
     c->prune = -1.0f;
     c->track = 0;
+    c->device = -1;
+    (void)hipGetDevice(&c->device);
+    void *own = nullptr;
+    (void)static_scratch(&own);          // dba_step_noalloc asks again (and reports) if this failed
+    c->lib_scratch = static_cast<unsigned char *>(own);
     // candidates of one sentence: at most k best + k row bests + k * phrases constraint tokens,
     // in whole chunks of 64 keys (at most 4224 keys = 33 KB of LDS)
     const int ncand_max = (k * (max_phrases + 2) + kWave - 1) / kWave * kWave;
@@ -694,7 +741,7 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
     p.first_bucket = at<u64>(c, L.bloom);
     p.bucket_tok = at<int32_t>(c, L.btok);
     p.rowlists = own_scratch ? reinterpret_cast<u64 *>(own_scratch) : at<u64>(c, L.rowlists);
-    p.conskeys = own_scratch ? reinterpret_cast<u64 *>(own_scratch) + (size_t)c->B * c->k * kWave : at<u64>(c, L.conskeys);
+    p.conskeys = own_scratch ? reinterpret_cast<u64 *>(own_scratch + kStaticListBytes) : at<u64>(c, L.conskeys);
     p.counters = at<unsigned int>(c, L.counters);
     p.out_token = out_token_dev;
     p.out_backptr = out_backptr_dev;
@@ -735,6 +782,30 @@ DBA_API int dba_step_fmt(dba_ctx *c, const void *logp_dev, int logp_format, int3
 {
     return step_impl(c, logp_dev, logp_format, out_token_dev, out_backptr_dev, out_score_dev, out_flags_dev,
                      nullptr);
+}
+
+DBA_API int dba_step_noalloc(dba_ctx *c, const void *logp_dev, int logp_format, int32_t *out_token_dev,
+                             int32_t *out_backptr_dev, float *out_score_dev, uint8_t *out_flags_dev)
+{
+    if (!c) return DBA_EINVAL;
+    if ((size_t)c->B * (size_t)c->k > kStaticRows)
+        return fail(c, DBA_EINVAL,
+                    "dba_step_noalloc: B*k = %zu beam rows exceed the %zu rows (DBA_NOALLOC_MAX_ROWS) the "
+                    "library's own scratch holds; use dba_step / dba_step_fmt",
+                    (size_t)c->B * (size_t)c->k, kStaticRows);
+    if (!c->lib_scratch) {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev != c->device)
+            return fail(c, DBA_ESTATE, "dba_step_noalloc: the device of dba_init (%d) must be current", c->device);
+        void *own = nullptr;
+        const hipError_t e = static_scratch(&own);
+        if (e != hipSuccess)
+            return fail(c, DBA_EHIP, "dba_step_noalloc: the library's scratch has no device address: %s",
+                        hipGetErrorString(e));
+        c->lib_scratch = static_cast<unsigned char *>(own);
+    }
+    return step_impl(c, logp_dev, logp_format, out_token_dev, out_backptr_dev, out_score_dev, out_flags_dev,
+                     c->lib_scratch);
 }
 
 DBA_API int dba_finalize(dba_ctx *c, int32_t *out_tokens_host, int32_t *out_len_host, float *out_score_host,

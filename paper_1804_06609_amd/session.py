@@ -39,11 +39,15 @@ class Session:
 
     _FORMATS = {torch.float32: _b.DBA_LOGP_F32, torch.float16: _b.DBA_LOGP_F16, torch.bfloat16: _b.DBA_LOGP_BF16}
 
-    def step(self, logp: torch.Tensor) -> None:
-        """Enqueue one step; logp is a contiguous device tensor [B,k,V] of fp32, fp16 or bf16."""
+    def step(self, logp: torch.Tensor, noalloc: bool = False) -> None:
+        """Enqueue one step; logp is a contiguous device tensor [B,k,V] of fp32, fp16 or bf16.
+        noalloc: through dba_step_noalloc (the library's own scratch instead of the workspace's)."""
         assert logp.is_cuda and logp.dtype in self._FORMATS and logp.is_contiguous()
         assert tuple(logp.shape) == (self.B, self.k, self.V)
-        if logp.dtype == torch.float32:
+        if noalloc:
+            _b.dba_step_noalloc(self.ctx, logp.data_ptr(), self._FORMATS[logp.dtype], self.out_token.data_ptr(),
+                                self.out_backptr.data_ptr(), self.out_score.data_ptr(), self.out_flags.data_ptr())
+        elif logp.dtype == torch.float32:
             _b.dba_step(self.ctx, logp.data_ptr(), self.out_token.data_ptr(), self.out_backptr.data_ptr(),
                         self.out_score.data_ptr(), self.out_flags.data_ptr())
         else:
