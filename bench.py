@@ -34,9 +34,20 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per step (fetched + written by its two launches) on the config-4 workload, from the
-# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled against a plain copy);
-# None whenever a kernel has changed since those counters were taken.
+# rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled against a plain copy), and
+# the digest of the kernel sources those counters were taken with: the line carries the figure only
+# while the sources are still those, null otherwise.
 TRAFFIC_BYTES_PER_LAUNCH = 168341936
+TRAFFIC_KERNEL_SHA16 = "0000000000000000"
+
+
+def kernel_sources_sha16() -> str:
+    import hashlib
+    m = hashlib.sha256()
+    for name in ("dba.hip", "dba_kernels.hpp", "wave_topk.hpp"):
+        with open(os.path.join(ROOT, "paper_1804_06609_amd", "csrc", name), "rb") as fh:
+            m.update(fh.read())
+    return m.hexdigest()[:16]
 
 
 def build_workload(cfg: int, cons_tokens):
@@ -81,6 +92,71 @@ def timed_steps(wl, dev, K, W, dlen, repeats, options=None):
     return float(np.median(wall)), float(np.median(evms))
 
 
+def flatness_pair(base_wl, dev, K, W, dlen, repeats):
+    """Sec. 1 / Table 1, inside the headline line: the same resident tensors decoded with exactly 1
+    and exactly 32 constraint tokens per sentence, the two legs taking turns; median event time per
+    step of each."""
+    import synth_inputs as si
+    ms = {"1": [], "32": []}
+    wls = {}
+    for c in (1, 32):
+        wl = si.make_config(4)
+        wl.constraints = si.fixed_total_constraints(base_wl.seed, base_wl.B, base_wl.V, c)
+        wl.eos_switch = 1 << 30
+        wls[str(c)] = wl
+    for _ in range(repeats):
+        for c in ("1", "32"):
+            _, ev_ms = timed_steps(wls[c], dev, K, W, dlen, 1)
+            ms[c].append(ev_ms / K)
+    med = {c: float(np.median(v)) for c, v in ms.items()}
+    return {"1": med["1"], "32": med["32"], "max_over_min": max(med.values()) / min(med.values()),
+            "unit": "ms/step (HIP events)", "steps": K, "repeats": repeats,
+            "what": "config-4 shapes and tensors, exactly 1 vs exactly 32 constraint tokens per sentence"}
+
+
+def gbs_simulation(args):
+    """Sec. 5 / Fig. 4 on synthetic inputs: the paper simulates grid beam search inside DBA with a
+    beam of b(C+1) and the adjustment off, and reports its time growing with the number of
+    constraints C while DBA at a fixed beam stays flat.  Here: B = 64, V = 32000, C single-token
+    constraints per sentence, base beam b = 4 -> k = b(C+1), adjustment off, against DBA at k = 20
+    with the adjustment on, same C; step time from HIP events, median of the repeats."""
+    import torch
+    import synth_inputs as si
+    from paper_1804_06609_amd import DBA_OPT_ADJUSTMENT
+    torch.cuda.set_device(0)
+    B, V, b = 64, 32000, 4
+    cache = {}
+
+    def tensors(k):
+        if k not in cache:
+            cache.clear()                      # one beam width resident at a time
+            gen = si.Workload(B=B, k=k, V=V, T=100, seed=si.BASE_SEED + 40 + k, constraints=[[] for _ in range(B)])
+            gen.eos_switch = 1 << 30
+            need = max(2, -(-600_000_000 // (4 * B * k * V)))      # more than the 256 MB Infinity Cache in rotation
+            cache[k] = [torch.from_numpy(gen.logp(t)).cuda() for t in range(min(need, 8))]
+        return cache[k]
+
+    Cs = (0, 1, 3, 7, 15)
+    rows = [{"C": C} for C in Cs]
+    # all legs of one beam width together, so that its tensors are generated once
+    legs = [("gbs_sim", i, b * (C + 1), 0) for i, C in enumerate(Cs)] + [("dba", i, 20, 1) for i in range(len(Cs))]
+    for name, i, k, adjust in legs:
+        cons = si.fixed_total_constraints(si.BASE_SEED + 50, B, V, Cs[i], max_len=1)
+        wl = si.Workload(B=B, k=k, V=V, T=100, seed=si.BASE_SEED + 60, constraints=cons)
+        wl.eos_switch = 1 << 30
+        _, ev_ms = timed_steps(wl, tensors(k), args.steps, args.warmup, 100, max(3, args.repeats),
+                               {DBA_OPT_ADJUSTMENT: adjust})
+        rows[i][name] = {"k": k, "us_per_step": ev_ms * 1e3 / args.steps}
+    print(json.dumps({"metric": "step time vs number of constraints: simulated grid beam search (beam b(C+1), no "
+                                "adjustment) against DBA at a fixed beam", "unit": "us/step",
+                      "config": {"workload": f"B={B} V={V}, C single-token constraints per sentence, base beam b={b}; "
+                                             "DBA at k=20"},
+                      "rows": rows, "steps": args.steps, "warmup": args.warmup, "n_gpus": 1, "data": "synthetic",
+                      "gbs_over_dba_at_C15": rows[-1]["gbs_sim"]["us_per_step"] / rows[-1]["dba"]["us_per_step"],
+                      "dba_max_over_min": max(r["dba"]["us_per_step"] for r in rows) /
+                      min(r["dba"]["us_per_step"] for r in rows)}))
+
+
 def flatness(args):
     """Sec. 1 / Table 1: the cost of a DBA step does not grow with the number of constraints."""
     import torch
@@ -115,6 +191,11 @@ def main():
     ap.add_argument("--flatness", action="store_true",
                     help="instead of the headline line: step time for 1,2,4,8,16,32 constraint tokens per "
                          "sentence (the paper's O(1)-in-C claim), one JSON line")
+    ap.add_argument("--gbs-sim", action="store_true",
+                    help="instead of the headline line: Sec. 5 / Fig. 4 on synthetic inputs - step time of the "
+                         "simulated grid beam search (beam 4(C+1), no adjustment) and of DBA at k=20 for "
+                         "C = 0,1,3,7,15 constraints, one JSON line")
+    ap.add_argument("--no-flatness", action="store_true", help="leave the 1-vs-32-token legs out of the headline line")
     ap.add_argument("--fused", action="store_true",
                     help="time the one-launch form of the step (DBA_OPT_FUSED_LAUNCH) instead of the default")
     ap.add_argument("--logp-format", choices=["f32", "f16", "bf16"], default="f32",
@@ -141,6 +222,8 @@ def main():
 
     if args.flatness:
         return flatness(args)
+    if args.gbs_sim:
+        return gbs_simulation(args)
 
     wl = build_workload(args.config, args.cons_tokens)
     B, k, V = wl.B, wl.k, wl.V
@@ -186,7 +269,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "f32" if esize == 4 else f"f32 sums, {args.logp_format} log-probs",
         "data": "synthetic",
         "config": {
             "workload": f"config{args.config}: B={B} k={k} V={V}, {ctok_desc} constraint tokens/sentence, "
@@ -201,7 +284,8 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": TRAFFIC_BYTES_PER_LAUNCH
-            if (args.config == 4 and args.cons_tokens is None and not args.fused and esize == 4) else None,
+            if (args.config == 4 and args.cons_tokens is None and not args.fused and esize == 4 and
+                kernel_sources_sha16() == TRAFFIC_KERNEL_SHA16) else None,
             "kernel": "dba_stream_kernel + dba_merge_kernel (the two launches of one step, back to back)"
                       if not args.fused else
                       "dba_step_fused_kernel (one launch per step: stream phase + merge phase)",
@@ -235,6 +319,10 @@ def main():
             "step_over_read": full_step_us / read_us,
         }
 
+    # Sec. 1 / Table 1: the step's cost does not depend on the number of constraints
+    if args.config == 4 and esize == 4 and not args.no_flatness and args.cons_tokens is None:
+        out["flatness"] = flatness_pair(wl, dev, max(K, 200), W, dlen, max(3, args.repeats))
+
     if args.copy_probe:
         dst = torch.empty_like(dev[0])
         for i in range(4):
@@ -250,17 +338,19 @@ def main():
         ses = Session(B, k, V, S, wl.eos_id, wl.pad_id, toks, poff, soff)
         if esize == 2:
             host = [oracle.widen16(x, args.logp_format) for x in bits]
-        t0 = time.perf_counter()
+        want = []                              # the oracle's beam after every step of the sample
+        cpu_s = 0.0
         for t in range(S):
+            t0 = time.perf_counter()
             ob.step(host[t % R], threads=threads)
-        cpu_s = time.perf_counter() - t0
+            cpu_s += time.perf_counter() - t0
+            want.append(tuple(ob.stacked(n).tobytes() for n in ("token", "backptr", "score", "flags", "met")))
         same = True
-        for t in range(S):
+        for t in range(S):                     # every step of the sample is compared, not only the last
             ses.step(dev[t % R])
-        g_tok, g_bp, g_sc, _ = ses.outputs()
-        same = (g_tok.tobytes() == ob.stacked("token").tobytes() and
-                g_bp.tobytes() == ob.stacked("backptr").tobytes() and
-                g_sc.tobytes() == ob.stacked("score").tobytes())
+            g_tok, g_bp, g_sc, g_fl = ses.outputs()
+            got = (g_tok.tobytes(), g_bp.tobytes(), g_sc.tobytes(), g_fl.tobytes(), ses.state()["met_mask"].tobytes())
+            same = same and got == want[t]
         ses.close()
         # the same oracle on one core, on a shorter sample (a step there takes about 0.4 s at config 4)
         S1 = 4 if args.config == 4 else 1
