@@ -18,6 +18,8 @@ FLAGS = [
     # packed fp32 VALU forms are kept off on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
+    # leading scalar kernel arguments arrive in registers at wave start (no load, no wait)
+    "-mllvm", "-amdgpu-kernarg-preload-count=8",
 ]
 
 

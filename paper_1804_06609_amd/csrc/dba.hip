@@ -18,29 +18,32 @@ using namespace dba;
 // ---------------------------------------------------------------------------
 // kernels
 // ---------------------------------------------------------------------------
-// Stream phase of one beam row by one workgroup of blockDim.x/64 waves: leaves the row's sorted
-// top keys in p.rowlists and the keys of its constraint tokens in p.conskeys.
+// Stream phase of one beam row (sentence b, slot h) by one workgroup of four waves: leaves the row's
+// sorted top keys in p.rowlists and the keys of its constraint tokens in p.conskeys.
 // U = 16-byte loads each lane keeps in flight per tile; FMT = element type of the log-probs.
 // PUBLISH: the two results are written with device-scope atomic stores, for readers in other
 // workgroups of the same launch.
+// logp, V, k, first_step are what the first loads need; the kernels take them as leading scalar
+// arguments, which the hardware hands over in registers at wave start (kernel-argument preload),
+// so that the first two tiles are requested before any argument has been read from memory.
 template <int U, int FMT, bool PUBLISH>
-__device__ __forceinline__ void stream_phase(const StepParams &p, int row, StreamSmem &sm)
+__device__ __forceinline__ void stream_phase(const StepParams &p, const void *logp, int V, int k, int first_step,
+                                             int b, int h, StreamSmem &sm)
 {
     typedef typename Logp<FMT>::elem_t elem_t;
-    const int b = row / p.k;
-    const int h = row - b * p.k;
+    const int row = b * k + h;
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    const int nwaves = (int)(blockDim.x >> 6);
+    constexpr int nwaves = kWavesPerBlock;
     const bool gatherer = wave == nwaves - 1;     // this wave also fetches the constraint tokens
 
     // the first two tiles of the row are requested before anything else: they need nothing of
     // the hypothesis, and the loads of the hypothesis (uniform, hence scalar loads the wave has to
     // wait for one after the other) would otherwise hold them back
-    const elem_t *__restrict__ logp_row = static_cast<const elem_t *>(p.logp) + (size_t)row * (size_t)p.V;
+    const elem_t *__restrict__ logp_row = static_cast<const elem_t *>(logp) + (size_t)row * (size_t)V;
     RowStream<U, FMT> rs;
-    const bool known_empty = p.first_step && h != 0;   // decoder-init leaves slots 1.. empty
-    if (!known_empty) rs.begin(logp_row, p.V, wave, nwaves);
+    const bool known_empty = first_step && h != 0;   // decoder-init leaves slots 1.. empty
+    if (!known_empty) rs.begin(logp_row, V, wave, nwaves);
     __builtin_amdgcn_sched_barrier(0);
     // then the hypothesis and its constraint bookkeeping (one wave, one lane per phrase)
     const float prev_ld = p.score_cur[row];
@@ -79,7 +82,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
         const float cx = cw >= 0 ? Logp<FMT>::widen_one(logp_row[cw]) : -INFINITY;
         // Sec. 3.3: no end-of-sentence before all constraints are met
         const int eos_block = (fin & kFinEosBlocked) ? p.eos_id : -1;
-        parked = rs.run(prev, eos_block, code_base, p.k, wave, nwaves, sm, st);
+        parked = rs.run(prev, eos_block, code_base, k, wave, nwaves, sm, st);
         const float cs = prev + cx;
         if (cw >= 0 && cs > -INFINITY)
             ckey = pack_sel(p.met_bits, cbank, ord_from_float(cs), code_base | (uint32_t)cw);
@@ -94,8 +97,8 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
         else *dst = ckey;
     }
     // workgroups are dealt out round-robin over the 256 compute units, so the ones sharing a
-    // compute unit differ in blockIdx / 256: let that pick the wave (hence the SIMD) that finishes
-    const int fin_wave = (int)((blockIdx.x >> 8) & (unsigned)(nwaves - 1));
+    // compute unit differ in (row / 256): let that pick the wave (hence the SIMD) that finishes
+    const int fin_wave = (row >> 8) & (nwaves - 1);
     const u64 acc = finish_row(sm, st.list, parked, wave, nwaves, fin_wave);
     if (wave == fin_wave) {
         // handed on in the form the merge phase works with (same order)
@@ -106,17 +109,18 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, int row, Strea
     }
 }
 
-// Two-launch form, first launch.  Grid: one workgroup per beam row.
+// Two-launch form, first launch.  Grid: (k, B) workgroups of 256 threads, one per beam row, in row
+// order.  k_first = k | first_step << 16.
 template <int U, int FMT>
-__global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
+__global__ __launch_bounds__(kBlock) void dba_stream_kernel(const void *logp, int V, int k_first, const StepParams p)
 {
     __shared__ StreamSmem sm;
-    stream_phase<U, FMT, false>(p, (int)blockIdx.x, sm);
+    stream_phase<U, FMT, false>(p, logp, V, k_first & 0xFFFF, k_first >> 16, (int)blockIdx.y, (int)blockIdx.x, sm);
 }
 
-// One-launch form.  Grid: one workgroup (256 threads) per beam row.  Every workgroup streams
-// its row; the one that delivers the last row of a sentence goes on to run that sentence's
-// merge phase, while other sentences are still streaming.
+// One-launch form.  Grid as above.  Every workgroup streams its row; the one that delivers the last
+// row of a sentence goes on to run that sentence's merge phase, while other sentences are still
+// streaming.
 //
 // Hand-over between workgroups without cache-wide fences: the row results are written with
 // device-scope atomic stores (written through to memory), each wave then waits for its stores
@@ -125,40 +129,44 @@ __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const StepParams p)
 // arrived and reads them with device-scope atomic loads (which bypass the non-coherent
 // caches).  No workgroup ever waits for another.
 template <int U, int FMT, int ROWS>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) void dba_step_fused_kernel(const StepParams p)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) void dba_step_fused_kernel(
+    const void *logp, int V, int k_first, const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     constexpr size_t kBytes = sizeof(StreamSmem) > sizeof(MergeSmem) ? sizeof(StreamSmem) : sizeof(MergeSmem);
     __shared__ __align__(16) unsigned char raw[kBytes];   // the phases use it one after the other
     __shared__ int last;
 
-    const int row = (int)blockIdx.x;
-    const int b = row / p.k;
+    const int b = (int)blockIdx.y;
+    const int k = k_first & 0xFFFF;
     // waves that stream go before waves that merge when both want to issue: a compute unit
     // serves its oldest waves first, and those would be the merging ones
     __builtin_amdgcn_s_setprio(2);
-    stream_phase<U, FMT, true>(p, row, *reinterpret_cast<StreamSmem *>(raw));
+    stream_phase<U, FMT, true>(p, logp, V, k, k_first >> 16, b, (int)blockIdx.x, *reinterpret_cast<StreamSmem *>(raw));
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's published stores are done
     __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned int seen =
             __hip_atomic_fetch_add(p.counters + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last = seen == (unsigned int)(p.k - 1) ? 1 : 0;
+        last = seen == (unsigned int)(k - 1) ? 1 : 0;
         if (last) __hip_atomic_store(p.counters + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (!last) return;
     __builtin_amdgcn_s_setprio(0);
-    merge_phase<ROWS, true>(p, b, *reinterpret_cast<MergeSmem *>(raw), reinterpret_cast<u64 *>(dyn_smem));
+    merge_phase<ROWS, true>(p, p.rowlists, p.conskeys, k, b, *reinterpret_cast<MergeSmem *>(raw),
+                            reinterpret_cast<u64 *>(dyn_smem));
 }
 
-// Merge phase.  Grid: one workgroup per sentence.
+// Merge phase.  Grid: one workgroup per sentence.  The pointers to the row lists and the beam width
+// come first: they are all the first loads need.
 template <int ROWS>
-__global__ __launch_bounds__(kBlock) void dba_merge_kernel(const StepParams p)
+__global__ __launch_bounds__(kBlock) void dba_merge_kernel(const u64 *rowlists, const u64 *conskeys, int k,
+                                                           const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ MergeSmem sm;
-    merge_phase<ROWS, false>(p, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
+    merge_phase<ROWS, false>(p, rowlists, conskeys, k, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
 }
 
 // Reference read: the largest element of each row, one workgroup per row, with the tile order and
@@ -486,7 +494,7 @@ int fail(dba_ctx *ctx, int code, const char *fmt, ...)
 
 bool shape_ok(int B, int k, int V, int N, int max_cons)
 {
-    return B >= 1 && k >= 1 && k <= DBA_MAX_BEAM && V >= 1 && N >= 1 && k <= V && max_cons >= 0 &&
+    return B >= 1 && B <= 65535 && k >= 1 && k <= DBA_MAX_BEAM && V >= 1 && N >= 1 && k <= V && max_cons >= 0 &&
            max_cons <= DBA_MAX_CONS_TOKENS;
 }
 
@@ -501,9 +509,10 @@ T *at(dba_ctx *c, size_t off)
 template <int FMT>
 static void launch_fused_fmt(int rows, dim3 grid, dim3 block, size_t dyn, hipStream_t st, const StepParams &p)
 {
-    if (rows == 4) dba_step_fused_kernel<kTileLoads, FMT, 4><<<grid, block, dyn, st>>>(p);
-    else if (rows == 8) dba_step_fused_kernel<kTileLoads, FMT, 8><<<grid, block, dyn, st>>>(p);
-    else dba_step_fused_kernel<kTileLoads, FMT, 16><<<grid, block, dyn, st>>>(p);
+    const int kf = p.k | (p.first_step << 16);
+    if (rows == 4) dba_step_fused_kernel<kTileLoads, FMT, 4><<<grid, block, dyn, st>>>(p.logp, p.V, kf, p);
+    else if (rows == 8) dba_step_fused_kernel<kTileLoads, FMT, 8><<<grid, block, dyn, st>>>(p.logp, p.V, kf, p);
+    else dba_step_fused_kernel<kTileLoads, FMT, 16><<<grid, block, dyn, st>>>(p.logp, p.V, kf, p);
 }
 
 static void launch_fused(int logp_format, int rows, dim3 grid, dim3 block, size_t dyn, hipStream_t st,
@@ -755,21 +764,22 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
 
     // 4 wavefronts per row, 4 loads of 16 bytes per lane and tile: 1280 rows x 4 waves fill the 1024 SIMDs
     // five deep with two 4 KB tiles in flight per wave (measured best on MI355X at V = 32000)
-    const dim3 grid((unsigned)(c->B * c->k)), block(kBlock);
+    const dim3 grid((unsigned)c->k, (unsigned)c->B), block(kBlock);      // row order: slot fastest
+    const int kf = p.k | (p.first_step << 16);
     // the merge phase is compiled for 4, 8 and 16 beam rows per wave: the smallest that holds k
     const int rows = c->k <= 16 ? 4 : (c->k <= 32 ? 8 : 16);
     if (c->fused && !own_scratch) {
         launch_fused(logp_format, rows, grid, block, c->dyn_smem, c->stream, p);
     } else {
         switch (logp_format) {
-            case DBA_LOGP_F16: dba_stream_kernel<kTileLoads, kFmtF16><<<grid, block, 0, c->stream>>>(p); break;
-            case DBA_LOGP_BF16: dba_stream_kernel<kTileLoads, kFmtBF16><<<grid, block, 0, c->stream>>>(p); break;
-            default: dba_stream_kernel<kTileLoads, kFmtF32><<<grid, block, 0, c->stream>>>(p); break;
+            case DBA_LOGP_F16: dba_stream_kernel<kTileLoads, kFmtF16><<<grid, block, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+            case DBA_LOGP_BF16: dba_stream_kernel<kTileLoads, kFmtBF16><<<grid, block, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+            default: dba_stream_kernel<kTileLoads, kFmtF32><<<grid, block, 0, c->stream>>>(p.logp, p.V, kf, p); break;
         }
         const dim3 mgrid((unsigned)c->B);
-        if (rows == 4) dba_merge_kernel<4><<<mgrid, block, c->dyn_smem, c->stream>>>(p);
-        else if (rows == 8) dba_merge_kernel<8><<<mgrid, block, c->dyn_smem, c->stream>>>(p);
-        else dba_merge_kernel<16><<<mgrid, block, c->dyn_smem, c->stream>>>(p);
+        if (rows == 4) dba_merge_kernel<4><<<mgrid, block, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+        else if (rows == 8) dba_merge_kernel<8><<<mgrid, block, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+        else dba_merge_kernel<16><<<mgrid, block, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_step: launch failed: %s", hipGetErrorString(e));

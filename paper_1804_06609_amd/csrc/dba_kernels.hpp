@@ -818,12 +818,39 @@ __device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kWavesPerBlock]
 // are unrolled, so a smaller bound keeps the code of small beams short.
 // COHERENT: the row lists were written by other workgroups of the same launch and are read
 // with device-scope atomic loads (see dba_step_fused_kernel).
+// rowlists, conskeys, k: what the first loads need (p.rowlists, p.conskeys and p.k, handed over apart).
 template <int ROWS, bool COHERENT>
-__device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSmem &sm, u64 *cand)
+__device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowlists, const u64 *conskeys, int k,
+                                            int b, MergeSmem &sm, u64 *cand)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // in a scalar register: row guards are scalar branches
-    const int k = p.k, mb = p.met_bits;
+    // the row lists first: the chain of this phase starts with them, and their addresses need nothing
+    // that has to be read from memory first
+    constexpr int kRowsPerWave = ROWS;
+    u64 rl[kRowsPerWave], ck[kRowsPerWave];
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        const int h = wave + i * kWavesPerBlock;
+        rl[i] = 0;
+        if (h < k) {
+            const size_t o = ((size_t)b * k + h) * kWave + lane;
+            if (COHERENT) rl[i] = __hip_atomic_load(rowlists + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else rl[i] = rowlists[o];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) {
+        const int h = wave + i * kWavesPerBlock;
+        ck[i] = 0;
+        if (h < k) {
+            const size_t o = ((size_t)b * k + h) * kWave + lane;
+            if (COHERENT) ck[i] = __hip_atomic_load(conskeys + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else ck[i] = conskeys[o];
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const int mb = p.met_bits;
     const int sel_shift = 64 - mb;
     const u64 body_mask = mb ? ((1ull << sel_shift) - 1ull) : ~0ull;
     const int fb = 32 - mb;
@@ -846,24 +873,6 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, int b, MergeSme
     const int ld_nxt = p.nxt_cur[rs];
     const int ld_len = p.len_cur[rs];
     const int ld_fin = p.fin_cur[rs];
-    constexpr int kRowsPerWave = ROWS;
-    u64 rl[kRowsPerWave], ck[kRowsPerWave];
-#pragma unroll
-    for (int i = 0; i < kRowsPerWave; ++i) {
-        const int h = wave + i * kWavesPerBlock;
-        rl[i] = 0;
-        ck[i] = 0;
-        if (h < k) {
-            const size_t o = ((size_t)b * k + h) * kWave + lane;
-            if (COHERENT) {
-                rl[i] = __hip_atomic_load(p.rowlists + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ck[i] = __hip_atomic_load(p.conskeys + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-                rl[i] = p.rowlists[o];
-                ck[i] = p.conskeys[o];
-            }
-        }
-    }
     // every load above is on its way before anything waits for one of them: the lists are
     // pinned here, or their loads would be moved down to the conditional code that uses them
 #pragma unroll
