@@ -136,3 +136,50 @@ def guarded_decode(case):
         for t in range(T):
             assert got[4 * t:4 * t + 4] == want[per_step * t:per_step * t + 4], (case, fused, t)
         assert [a.tobytes() for a in fin] == want[-4:]
+
+
+def test_a_decode_replayed_from_a_hip_graph_matches_eager_launches():
+    """A step enqueues two kernels and nothing else (no allocation, no memset, no copy), so a decode can
+    be recorded into a HIP graph by a caller who wants to.  Steps 1..T-1 of a decode are recorded once and replayed three times, each
+    time from the device state after step 0 (the workspace is copied back, with eager work and
+    synchronisations in between); every replay must leave the beam, the state and the end of
+    decoding of the eager decode."""
+    import torch
+    from paper_1804_06609_amd.session import Session
+    wl = si.make_config(3, T=24)
+    wl.eos_switch = 14
+    toks, poff, soff = wl.csr()
+    dev = [torch.from_numpy(wl.logp(t)).cuda() for t in range(wl.T)]
+    eager = Session(wl.B, wl.k, wl.V, wl.T, wl.eos_id, wl.pad_id, toks, poff, soff)
+    for t in range(wl.T):
+        eager.step(dev[t])
+    want_out = [a.tobytes() for a in eager.outputs()]
+    want_state = {n: a.tobytes() for n, a in eager.state().items()}
+    want_fin = [np.asarray(a).tobytes() for a in eager.finalize()]
+    want_stop = eager.finished().tobytes()
+    eager.close()
+
+    side = torch.cuda.Stream()
+    ses = Session(wl.B, wl.k, wl.V, wl.T, wl.eos_id, wl.pad_id, toks, poff, soff, stream=side)
+    with torch.cuda.stream(side):
+        ses.step(dev[0])
+    torch.cuda.synchronize()
+    after_step0 = ses.workspace.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for t in range(1, wl.T):
+            ses.step(dev[t])
+    torch.cuda.synchronize()
+    for replay in range(3):
+        ses.workspace.copy_(after_step0)                  # eager work between the replays
+        for o in (ses.out_token, ses.out_backptr, ses.out_score, ses.out_flags):
+            o.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        torch.cuda.synchronize()
+        assert [a.tobytes() for a in ses.outputs()] == want_out, replay
+        assert {n: a.tobytes() for n, a in ses.state().items()} == want_state, replay
+        assert ses.finished().tobytes() == want_stop, replay
+        assert [np.asarray(a).tobytes() for a in ses.finalize()] == want_fin, replay
+    ses.close()
