@@ -48,16 +48,27 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, const void *lo
     // then the hypothesis and its constraint bookkeeping (one wave, one lane per phrase)
     const float prev_ld = p.score_cur[row];
     const int fin_ld = p.fin_cur[row];
-    u64 g_met = 0, g_inc = 0, g_sfl = 0;
-    int g_ipq = -1, g_nxt = -1, g_ftok = -1, g_P = 0;
-    if (gatherer) {
+    // workgroups are dealt out round-robin over the 256 compute units, so the ones sharing a
+    // compute unit differ in (row / 256): let that pick the wave (hence the SIMD) that finishes the row
+    const int fin_wave = (row >> 8) & (nwaves - 1);
+    const bool finisher = wave == fin_wave;
+    u64 g_met = 0, g_inc = 0, g_sfl = 0, t_bucket = 0;
+    int g_ipq = -1, g_nxt = -1, g_ftok = -1, g_P = 0, t_btok = -1;
+    if (gatherer || finisher) {
         g_met = p.met_cur[row];
         g_inc = p.inc_cur[row];
         g_ipq = p.ipq_cur[row];
         g_nxt = p.nxt_cur[row];
-        g_P = p.nphr[b];
         g_ftok = p.first_tok[(size_t)b * kMaxCons + lane];
+    }
+    if (gatherer) {
+        g_P = p.nphr[b];
         g_sfl = p.same_first_lower[(size_t)b * kMaxCons + lane];
+    }
+    if (finisher) {
+        // lane j: the phrases whose first token has low six bits j, and that token where they agree on it
+        t_bucket = p.first_bucket[(size_t)b * kMaxCons + lane];
+        t_btok = p.bucket_tok[(size_t)b * kMaxCons + lane];
     }
 
     // the row's hypothesis: wave-uniform by construction, made so for the compiler
@@ -96,13 +107,31 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, const void *lo
         if (PUBLISH) __hip_atomic_store(dst, ckey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else *dst = ckey;
     }
-    // workgroups are dealt out round-robin over the 256 compute units, so the ones sharing a
-    // compute unit differ in (row / 256): let that pick the wave (hence the SIMD) that finishes
-    const int fin_wave = (row >> 8) & (nwaves - 1);
     const u64 acc = finish_row(sm, st.list, parked, wave, nwaves, fin_wave);
-    if (wave == fin_wave) {
-        // handed on in the form the merge phase works with (same order)
-        const u64 out = body_from_rowkey(p.met_bits, acc);
+    if (finisher) {
+        // Handed on as selection keys: every listed sum with the bank it would land in - the
+        // constraints met once the hypothesis has emitted that token (add(), Sec. 3.1).  Each lane
+        // looks its own token up in the sentence's table of first tokens, which the lanes of this
+        // wave hold (lane j = bucket j): the phrases it could begin, then the count.
+        // (every lane takes every step, so that any lane's table entry can be read)
+        const int nmet = __popcll(g_met);
+        const bool extends = !(fin & kFinFinished) && acc != 0;      // not the carried-over key of a finished row
+        const int w = extends ? (int)(key_flat(acc) & ((1u << p.tok_bits) - 1u)) : 0;
+        const int same = __shfl(t_btok, w & 63, kWave);
+        const u64 bucket = ((u64)(uint32_t)__shfl((int)(uint32_t)(t_bucket >> 32), w & 63, kWave) << 32) |
+                           (u64)(uint32_t)__shfl((int)(uint32_t)t_bucket, w & 63, kWave);
+        u64 match = (extends && same == w) ? bucket : 0;
+        u64 todo = (extends && same == -2) ? bucket : 0;   // the bucket's phrases begin differently: one by one
+        while (__ballot(todo != 0)) {
+            const int j = todo ? __ffsll((long long)todo) - 1 : 0;
+            const int first = __shfl(g_ftok, j, kWave);
+            if (todo && first == w) match |= 1ull << j;
+            todo &= todo - 1;
+        }
+        const int bank = !extends ? nmet
+                                  : nmet_after(nmet, g_ipq < 0 ? -1 : (g_ipq >> 8), g_ipq < 0 ? 0 : (g_ipq & 255),
+                                               w == g_nxt, match, g_inc);
+        const u64 out = sel_from_rowkey(p.met_bits, bank, acc);
         u64 *dst = p.rowlists + (size_t)row * kWave + lane;
         if (PUBLISH) __hip_atomic_store(dst, out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else *dst = out;

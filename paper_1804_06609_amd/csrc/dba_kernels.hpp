@@ -114,8 +114,6 @@ struct MergeSmem {
     uint32_t ws[kWavesPerBlock][kWave];      // every wave's best score images
     uint32_t wf[kWavesPerBlock][kWave];      // and the greatest images its merges dropped
     uint32_t ws2[kWavesPerBlock][kWave];     // every wave's best low words among tied keys
-    // every wave's own candidates from sources 1 and 3: at most k of the k best plus one per row
-    u64 gath[kWavesPerBlock][kMaxBeam + kMaxBeam / kWavesPerBlock];
     HypState hyp[kMaxBeam];
     u64 sel[kMaxBeam];
     ConsTab ct;
@@ -712,12 +710,12 @@ __device__ __forceinline__ u64 pack_sel(int met_bits, int bank, uint32_t ord, ui
     return v;
 }
 
-// stream-phase key (score image << 32 | ~flat) -> body of a selection key (score image << fb | ~flat
-// in fb bits); order-preserving; 0 stays 0
-__device__ __forceinline__ u64 body_from_rowkey(int met_bits, u64 key)
+// stream-phase key (score image << 32 | ~flat) -> selection key in bank `bank` (its body - score image
+// << fb | ~flat in fb bits - orders like the stream-phase key); 0 stays 0
+__device__ __forceinline__ u64 sel_from_rowkey(int met_bits, int bank, u64 key)
 {
     if (key == 0) return 0;
-    return pack_sel(met_bits, 0, (uint32_t)(key >> 32), key_flat(key));
+    return pack_sel(met_bits, bank, (uint32_t)(key >> 32), key_flat(key));
 }
 
 // The phrases whose first token is w (w < 0: none), as a bit mask.  Every lane looks its own
@@ -973,8 +971,8 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
             if (wave + i * kWavesPerBlock < k) {
-                const u64 best = read_lane(rl[i], 0);
-                gm |= (rl[i] >= keep_from ? 1u : 0u) << i;
+                const u64 best = read_lane(rl[i], 0) & body_mask;
+                gm |= ((rl[i] & body_mask) >= keep_from ? 1u : 0u) << i;
                 const u64 body = ck[i] & body_mask;
                 const bool valid = body - 1 < below - 1 && body != best;      // (an empty place holds 0)
                 cm |= (valid ? 1u : 0u) << i;
@@ -997,12 +995,13 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
                     const int l = __ffsll((long long)tied) - 1;
                     tied &= tied - 1;
                     const u64 one = read_lane(body, l);
-                    if (__ballot(rl[i] == one) != 0 && lane == l) cm &= ~(1u << i);
+                    if (__ballot((rl[i] & body_mask) == one) != 0 && lane == l) cm &= ~(1u << i);
                 }
             }
         }
     }
-    constexpr int kStrip = kMaxBeam + kMaxBeam / kWavesPerBlock;
+    // Both kinds of key arrive with their bank (the constraints met once the token is placed, worked
+    // out with add() by the row's own workgroup, Sec. 3.1), so a kept key goes straight to its place.
     const int g = __popc(gm), c = __popc(cm);              // this lane's keys from sources 1 and 3, from source 2
     const int g_incl = wave_inclusive_sum(g), c_incl = wave_inclusive_sum(c);
     const int n13_all = __builtin_amdgcn_readlane(g_incl, kWave - 1);
@@ -1010,42 +1009,21 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
     int at = 0;
     if (lane == 0 && total > 0) at = atomicAdd(&sm.ncand, total);
     at = __builtin_amdgcn_readfirstlane(at);
-    // The counts cannot exceed the room they index (at most k keys reach tau, a row adds one more
-    // only if none of its keys does, the host sized `cand` for every source) as long as the row
-    // lists are what the stream phase writes: decreasing, distinct keys.  A wave that finds
-    // otherwise writes nothing: a damaged list costs a wrong beam, not a stray write.
-    const int n13 = n13_all <= kStrip ? n13_all : 0;
-    const bool fits = n13_all <= kStrip && at + total <= p.cand_cap;
-    if (n13_all <= kStrip) {
-        int to = g_incl - g;
+    // The count cannot exceed the room (at most k keys reach tau, a row adds one more only if none of
+    // its keys does, the host sized `cand` for every source) as long as the row lists are what the
+    // stream phase writes: decreasing, distinct keys.  A wave that finds otherwise writes nothing: a
+    // damaged list costs a wrong beam, not a stray write.  (The bank tables hold every value the
+    // bank field of a key can take.)
+    if (at + total <= p.cand_cap) {
+        int to = at + g_incl - g;
 #pragma unroll
-        for (int i = 0; i < kRowsPerWave; ++i)
-            if (wave + i * kWavesPerBlock < k && ((gm >> i) & 1u)) sm.gath[wave][to++] = rl[i];
-    }
-    __builtin_amdgcn_wave_barrier();                   // the wave reads back what its lanes wrote
-    for (int base = 0; base < n13; base += kWave) {
-        const int idx = base + lane;
-        const bool valid = idx < n13;
-        const u64 body = valid ? sm.gath[wave][idx] : 0ull;
-        int h = 0, w = -1;
-        if (valid) {
-            const uint32_t code = flatmask - ((uint32_t)body & flatmask);
-            h = min((int)(code >> p.tok_bits), kMaxBeam - 1);
-            w = (int)(code & tokmask);
+        for (int i = 0; i < kRowsPerWave; ++i) {
+            if (wave + i * kWavesPerBlock < k && ((gm >> i) & 1u)) {
+                cand[to++] = rl[i];
+                atomicAdd(&sm.cnt[mb ? (int)(rl[i] >> sel_shift) : 0], 1);    // bank = constraints met (Sec. 3.1)
+            }
         }
-        const HypState hs = sm.hyp[h];
-        const u64 match = first_token_matches(w, sm);
-        if (valid) {
-            int bank = hs.misc >> 8;
-            if (!(hs.misc & kFinFinished))
-                bank = nmet_after(bank, hs.ipq < 0 ? -1 : (hs.ipq >> 8), hs.ipq < 0 ? 0 : (hs.ipq & 255),
-                                  w == hs.nxt, match, hs.inc);
-            if (fits) cand[at + idx] = mb ? (body | ((u64)bank << sel_shift)) : body;
-            atomicAdd(&sm.cnt[bank], 1);                  // bank = constraints met (Sec. 3.1)
-        }
-    }
-    if (fits) {
-        int to = at + n13 + c_incl - c;
+        to = at + n13_all + c_incl - c;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
             if (wave + i * kWavesPerBlock < k && ((cm >> i) & 1u)) {
