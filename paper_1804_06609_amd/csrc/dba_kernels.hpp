@@ -875,6 +875,16 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
     // pinned here, or their loads would be moved down to the conditional code that uses them
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) asm volatile("" : "+v"(rl[i]), "+v"(ck[i]));
+    // ---- source 1: the sentence's k best (Sec. 3.1 item 1) = top k of the union of the row
+    // lists.  All that is needed of them is the bar tau a key has to reach to be among them.
+    // The k-th best SCORE comes from merging the 32-bit score images alone.  If the keys with
+    // that score or a better one are exactly k, that is the bar.  Otherwise several keys tie
+    // for the last places: the same merge over the low words (the coordinates, complemented)
+    // of the keys with that score finds the last one that gets in. -------------------------
+    uint32_t fell = 0;
+    uint32_t accs = wave_best64<kRowsPerWave, (kRowsPerWave > 8)>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
+    // the sentence's tables and beam go to LDS only now: their loads were issued after those of the
+    // row lists and arrive later, and the merges above needed none of them
     if (tid <= kMaxCons) sm.ct.poff[tid] = ld_poff;
     if (tid < 2 * kMaxCons) {
         sm.cnt[tid] = 0;
@@ -902,15 +912,6 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         hs.misc = (ld_fin & kFinFinished) | (__popcll(ld_met) << 8);
         sm.hyp[tid] = hs;
     }
-
-    // ---- source 1: the sentence's k best (Sec. 3.1 item 1) = top k of the union of the row
-    // lists.  All that is needed of them is the bar tau a key has to reach to be among them.
-    // The k-th best SCORE comes from merging the 32-bit score images alone.  If the keys with
-    // that score or a better one are exactly k, that is the bar.  Otherwise several keys tie
-    // for the last places: the same merge over the low words (the coordinates, complemented)
-    // of the keys with that score finds the last one that gets in. -------------------------
-    uint32_t fell = 0;
-    uint32_t accs = wave_best64<kRowsPerWave, (kRowsPerWave > 8)>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
     sm.wf[wave][lane] = fell;
     accs = block_best64<false>(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
     const int C = sm.ct.poff[P];
