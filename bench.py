@@ -232,8 +232,6 @@ def main():
     ap.add_argument("--no-flatness", action="store_true", help="leave the 1-vs-32-token legs out of the headline line")
     ap.add_argument("--no-concurrent", action="store_true",
                     help="leave the legs with 2 and 3 decodes in flight out of the headline line")
-    ap.add_argument("--fused", action="store_true",
-                    help="time the one-launch form of the step (DBA_OPT_FUSED_LAUNCH) instead of the default")
     ap.add_argument("--logp-format", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of the resident log-prob tensors (default f32, the headline workload); "
                          "16-bit tensors halve the algorithmic bytes, the sums stay fp32")
@@ -279,9 +277,7 @@ def main():
         esize = 2
     torch.cuda.synchronize()
 
-    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
-    options = {DBA_OPT_FUSED_LAUNCH: 1} if args.fused else None
-    wall_s, ev_ms = timed_steps(wl, dev, K, W, dlen, args.repeats, options)
+    wall_s, ev_ms = timed_steps(wl, dev, K, W, dlen, args.repeats)
 
     # algorithmic bytes: every live row's V log-probs once.  The first step of a decode has one
     # live row, all later steps k (EOS never fires in this workload).
@@ -320,11 +316,9 @@ def main():
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": TRAFFIC_BYTES_PER_LAUNCH
-            if (args.config == 4 and args.cons_tokens is None and not args.fused and esize == 4 and
+            if (args.config == 4 and args.cons_tokens is None and esize == 4 and
                 kernel_sources_sha16() == TRAFFIC_KERNEL_SHA16) else None,
-            "kernel": "dba_stream_kernel + dba_merge_kernel (the two launches of one step, back to back)"
-                      if not args.fused else
-                      "dba_step_fused_kernel (one launch per step: stream phase + merge phase)",
+            "kernel": "dba_stream_kernel + dba_merge_kernel (the two launches of one step, back to back)",
             "us_per_launch": ev_ms * 1e3 / launches,
             "algorithmic_bytes_per_launch": bytes_total / launches,
         },
@@ -360,7 +354,7 @@ def main():
         out["flatness"] = flatness_pair(wl, dev, max(K, 200), W, dlen, max(3, args.repeats))
 
     # more than one decode in flight: the same kernels, the serial chain of one decode hidden by another
-    if args.config == 4 and esize == 4 and not args.no_concurrent and args.cons_tokens is None and not args.fused:
+    if args.config == 4 and esize == 4 and not args.no_concurrent and args.cons_tokens is None:
         cd = {}
         for n in (2, 3):
             us = concurrent_decodes(wl, dev, max(K, 200), W, dlen, max(3, args.repeats), n)

@@ -134,8 +134,8 @@ DBA_API int dba_step_fmt(dba_ctx *ctx, const void *logp_dev, int logp_format, in
  * the first launch to the second is not taken from the caller's workspace but from a fixed array
  * inside the library, 8 MiB per GPU, resolved once per device.)  Same arguments, same results and
  * the same asynchronous behaviour as dba_step_fmt; calls may be mixed with dba_step / dba_step_fmt
- * on the same ctx from step to step.  The step always runs as two launches (DBA_OPT_FUSED_LAUNCH is
- * ignored).  Nothing in the array has to start at zero: every step overwrites what it reads.
+ * on the same ctx from step to step.  Nothing in the array has to start at zero: every step
+ * overwrites what it reads.
  * Limits: B*k <= DBA_NOALLOC_MAX_ROWS, else DBA_EINVAL with a message (no launch).  All contexts on
  * one GPU share that GPU's array: steps of different contexts that overlap in time (different
  * streams) race on it - keep such steps on one stream or use dba_step.  The device that was current
@@ -180,10 +180,6 @@ DBA_API int dba_get_state(dba_ctx *ctx, float *score_host, uint64_t *met_mask_ho
  * Options, settable between dba_init and the first dba_step (DBA_ESTATE afterwards,
  * DBA_EINVAL for an unknown option or a NaN value).  The defaults give the bare
  * algorithm of Alg. 2; the others are the settings of the paper's experiments.
- *   DBA_OPT_FUSED_LAUNCH        0 (default): a step is two launches - the kernel that streams
- *                               the log-probs, then the per-sentence merge kernel; non-zero: one
- *                               launch, in which the workgroup delivering a sentence's last row
- *                               runs the merge.  Same results; two launches measured faster.
  *   DBA_OPT_ADJUSTMENT          1 (default): bank sizes are adjusted as in Sec. 3.2; 0: they stay
  *                               at the base split and a bank that cannot fill its slots leaves
  *                               them empty - with k = b(C+1) the grid-beam-search simulation of
@@ -209,7 +205,6 @@ DBA_API int dba_get_state(dba_ctx *ctx, float *score_host, uint64_t *met_mask_ho
  *                               keeps the earliest step, then the lowest slot - and dba_finalize
  *                               returns it (Sec. 3.3: the highest-scoring completed item is returned).
  */
-#define DBA_OPT_FUSED_LAUNCH 1
 #define DBA_OPT_ADJUSTMENT 2
 #define DBA_OPT_NORMALIZE_FINISHED 3
 #define DBA_OPT_PRUNE_THRESHOLD 4

@@ -21,12 +21,10 @@ using namespace dba;
 // Stream phase of one beam row (sentence b, slot h) by one workgroup of four waves: leaves the row's
 // sorted top keys in p.rowlists and the keys of its constraint tokens in p.conskeys.
 // U = 16-byte loads each lane keeps in flight per tile; FMT = element type of the log-probs.
-// PUBLISH: the two results are written with device-scope atomic stores, for readers in other
-// workgroups of the same launch.
 // logp, V, k, first_step are what the first loads need; the kernels take them as leading scalar
 // arguments, which the hardware hands over in registers at wave start (kernel-argument preload),
 // so that the first two tiles are requested before any argument has been read from memory.
-template <int U, int FMT, bool PUBLISH>
+template <int U, int FMT>
 __device__ __forceinline__ void stream_phase(const StepParams &p, const void *logp, int V, int k, int first_step,
                                              int b, int h, StreamSmem &sm)
 {
@@ -103,9 +101,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, const void *lo
         st.list = make_key(prev + 0.0f, code_base | (uint32_t)p.pad_id);
     }
     if (gatherer) {
-        u64 *dst = p.conskeys + (size_t)row * kMaxCons + lane;
-        if (PUBLISH) __hip_atomic_store(dst, ckey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        else *dst = ckey;
+        p.conskeys[(size_t)row * kMaxCons + lane] = ckey;
     }
     const u64 acc = finish_row(sm, st.list, parked, wave, nwaves, fin_wave);
     if (finisher) {
@@ -131,63 +127,20 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, const void *lo
         const int bank = !extends ? nmet
                                   : nmet_after(nmet, g_ipq < 0 ? -1 : (g_ipq >> 8), g_ipq < 0 ? 0 : (g_ipq & 255),
                                                w == g_nxt, match, g_inc);
-        const u64 out = sel_from_rowkey(p.met_bits, bank, acc);
-        u64 *dst = p.rowlists + (size_t)row * kWave + lane;
-        if (PUBLISH) __hip_atomic_store(dst, out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        else *dst = out;
+        p.rowlists[(size_t)row * kWave + lane] = sel_from_rowkey(p.met_bits, bank, acc);
     }
 }
 
-// Two-launch form, first launch.  Grid: (k, B) workgroups of 256 threads, one per beam row, in row
+// First launch of a step.  Grid: (k, B) workgroups of 256 threads, one per beam row, in row
 // order.  k_first = k | first_step << 16.
 template <int U, int FMT>
 __global__ __launch_bounds__(kBlock) void dba_stream_kernel(const void *logp, int V, int k_first, const StepParams p)
 {
     __shared__ StreamSmem sm;
-    stream_phase<U, FMT, false>(p, logp, V, k_first & 0xFFFF, k_first >> 16, (int)blockIdx.y, (int)blockIdx.x, sm);
+    stream_phase<U, FMT>(p, logp, V, k_first & 0xFFFF, k_first >> 16, (int)blockIdx.y, (int)blockIdx.x, sm);
 }
 
-// One-launch form.  Grid as above.  Every workgroup streams its row; the one that delivers the last
-// row of a sentence goes on to run that sentence's merge phase, while other sentences are still
-// streaming.
-//
-// Hand-over between workgroups without cache-wide fences: the row results are written with
-// device-scope atomic stores (written through to memory), each wave then waits for its stores
-// to be acknowledged, the workgroup meets at a barrier, and one thread bumps the sentence's
-// arrival counter with a device-scope atomic.  Whoever reads k-1 there knows all k rows have
-// arrived and reads them with device-scope atomic loads (which bypass the non-coherent
-// caches).  No workgroup ever waits for another.
-template <int U, int FMT, int ROWS>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) void dba_step_fused_kernel(
-    const void *logp, int V, int k_first, const StepParams p)
-{
-    extern __shared__ __align__(16) unsigned char dyn_smem[];
-    constexpr size_t kBytes = sizeof(StreamSmem) > sizeof(MergeSmem) ? sizeof(StreamSmem) : sizeof(MergeSmem);
-    __shared__ __align__(16) unsigned char raw[kBytes];   // the phases use it one after the other
-    __shared__ int last;
-
-    const int b = (int)blockIdx.y;
-    const int k = k_first & 0xFFFF;
-    // waves that stream go before waves that merge when both want to issue: a compute unit
-    // serves its oldest waves first, and those would be the merging ones
-    __builtin_amdgcn_s_setprio(2);
-    stream_phase<U, FMT, true>(p, logp, V, k, k_first >> 16, b, (int)blockIdx.x, *reinterpret_cast<StreamSmem *>(raw));
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's published stores are done
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int seen =
-            __hip_atomic_fetch_add(p.counters + b, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last = seen == (unsigned int)(k - 1) ? 1 : 0;
-        if (last) __hip_atomic_store(p.counters + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    if (!last) return;
-    __builtin_amdgcn_s_setprio(0);
-    merge_phase<ROWS, true>(p, p.rowlists, p.conskeys, k, b, *reinterpret_cast<MergeSmem *>(raw),
-                            reinterpret_cast<u64 *>(dyn_smem));
-}
-
-// Merge phase.  Grid: one workgroup per sentence.  The pointers to the row lists and the beam width
+// Second launch of a step: the merge phase.  Grid: one workgroup per sentence.  The pointers to the row lists and the beam width
 // come first: they are all the first loads need.
 template <int ROWS>
 __global__ __launch_bounds__(kBlock) void dba_merge_kernel(const u64 *rowlists, const u64 *conskeys, int k,
@@ -195,7 +148,7 @@ __global__ __launch_bounds__(kBlock) void dba_merge_kernel(const u64 *rowlists, 
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ MergeSmem sm;
-    merge_phase<ROWS, false>(p, rowlists, conskeys, k, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
+    merge_phase<ROWS>(p, rowlists, conskeys, k, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
 }
 
 // Reference read: the largest element of each row, one workgroup per row, with the tile order and
@@ -278,8 +231,7 @@ __global__ void dba_wave_select_kernel(int n_cases, const u64 *keys, const float
 // decoder-init: slot 0 of every sentence is a live, empty hypothesis with score +0.0
 __global__ void dba_init_state_kernel(int B, int k, const int32_t *phr_off, const int32_t *nphr, float *score,
                                       u64 *met, int32_t *ipq, int32_t *len, uint8_t *fin, u64 *inc,
-                                      int32_t *nxt, unsigned int *counters, uint8_t *all_finished,
-                                      BestCompleted *best)
+                                      int32_t *nxt, uint8_t *all_finished, BestCompleted *best)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < B * k) {
@@ -295,7 +247,6 @@ __global__ void dba_init_state_kernel(int B, int k, const int32_t *phr_off, cons
         nxt[i] = -1;
     }
     if (i < B) {
-        counters[i] = 0;
         all_finished[i] = 0;
         BestCompleted none = {};
         best[i] = none;
@@ -395,7 +346,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct Layout {
     size_t score[2], met[2], ipq[2], len[2], fin[2], inc[2], nxt[2];
-    size_t cons_tok, phr_off, nphr, ftok, sfl, bloom, btok, rowlists, conskeys, counters;
+    size_t cons_tok, phr_off, nphr, ftok, sfl, bloom, btok, rowlists, conskeys;
     size_t hist_token, hist_backptr;
     size_t fin_tokens, fin_len, fin_score, fin_status, all_finished, best;
     size_t total;
@@ -428,7 +379,6 @@ Layout make_layout(size_t B, size_t k, size_t N)
     L.btok = take(B * kMaxCons * sizeof(int32_t));
     L.rowlists = take(B * k * kWave * sizeof(u64));
     L.conskeys = take(B * k * kMaxCons * sizeof(u64));
-    L.counters = take(B * sizeof(unsigned int));
     L.hist_token = take(N * B * k * sizeof(int32_t));
     L.hist_backptr = take(N * B * k * sizeof(int32_t));
     L.fin_tokens = take(B * N * sizeof(int32_t));
@@ -495,7 +445,6 @@ struct dba_ctx {
     int tok_bits;
     int max_phrases;
     int steps;
-    int fused;                          // DBA_OPT_FUSED_LAUNCH
     int adjust;                         // DBA_OPT_ADJUSTMENT
     int normalize;                      // DBA_OPT_NORMALIZE_FINISHED
     float prune;                        // DBA_OPT_PRUNE_THRESHOLD (< 0: off)
@@ -534,25 +483,6 @@ T *at(dba_ctx *c, size_t off)
 }
 
 }  // namespace
-
-template <int FMT>
-static void launch_fused_fmt(int rows, dim3 grid, dim3 block, size_t dyn, hipStream_t st, const StepParams &p)
-{
-    const int kf = p.k | (p.first_step << 16);
-    if (rows == 4) dba_step_fused_kernel<kTileLoads, FMT, 4><<<grid, block, dyn, st>>>(p.logp, p.V, kf, p);
-    else if (rows == 8) dba_step_fused_kernel<kTileLoads, FMT, 8><<<grid, block, dyn, st>>>(p.logp, p.V, kf, p);
-    else dba_step_fused_kernel<kTileLoads, FMT, 16><<<grid, block, dyn, st>>>(p.logp, p.V, kf, p);
-}
-
-static void launch_fused(int logp_format, int rows, dim3 grid, dim3 block, size_t dyn, hipStream_t st,
-                         const StepParams &p)
-{
-    switch (logp_format) {
-        case DBA_LOGP_F16: launch_fused_fmt<kFmtF16>(rows, grid, block, dyn, st, p); break;
-        case DBA_LOGP_BF16: launch_fused_fmt<kFmtBF16>(rows, grid, block, dyn, st, p); break;
-        default: launch_fused_fmt<kFmtF32>(rows, grid, block, dyn, st, p); break;
-    }
-}
 
 extern "C" {
 
@@ -659,7 +589,6 @@ static int init_impl(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->ws = static_cast<unsigned char *>(workspace_dev);
     c->L = L;
     c->stream = static_cast<hipStream_t>(hip_stream);
-    c->fused = 0;
     c->adjust = 1;
     c->normalize = 0;
     c->prune = -1.0f;
@@ -694,7 +623,7 @@ static int init_impl(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
             B, k, at<int32_t>(c, L.phr_off), at<int32_t>(c, L.nphr), at<float>(c, L.score[0]),
             at<u64>(c, L.met[0]), at<int32_t>(c, L.ipq[0]), at<int32_t>(c, L.len[0]),
             at<uint8_t>(c, L.fin[0]), at<u64>(c, L.inc[0]), at<int32_t>(c, L.nxt[0]),
-            at<unsigned int>(c, L.counters), at<uint8_t>(c, L.all_finished), at<BestCompleted>(c, L.best));
+            at<uint8_t>(c, L.all_finished), at<BestCompleted>(c, L.best));
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);   // host tables are freed on return
@@ -780,7 +709,6 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
     p.bucket_tok = at<int32_t>(c, L.btok);
     p.rowlists = own_scratch ? reinterpret_cast<u64 *>(own_scratch) : at<u64>(c, L.rowlists);
     p.conskeys = own_scratch ? reinterpret_cast<u64 *>(own_scratch + kStaticListBytes) : at<u64>(c, L.conskeys);
-    p.counters = at<unsigned int>(c, L.counters);
     p.out_token = out_token_dev;
     p.out_backptr = out_backptr_dev;
     p.out_score = out_score_dev;
@@ -797,9 +725,7 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
     const int kf = p.k | (p.first_step << 16);
     // the merge phase is compiled for 4, 8 and 16 beam rows per wave: the smallest that holds k
     const int rows = c->k <= 16 ? 4 : (c->k <= 32 ? 8 : 16);
-    if (c->fused && !own_scratch) {
-        launch_fused(logp_format, rows, grid, block, c->dyn_smem, c->stream, p);
-    } else {
+    {
         switch (logp_format) {
             case DBA_LOGP_F16: dba_stream_kernel<kTileLoads, kFmtF16><<<grid, block, 0, c->stream>>>(p.logp, p.V, kf, p); break;
             case DBA_LOGP_BF16: dba_stream_kernel<kTileLoads, kFmtBF16><<<grid, block, 0, c->stream>>>(p.logp, p.V, kf, p); break;
@@ -923,7 +849,6 @@ DBA_API int dba_set_option(dba_ctx *c, int option, double value)
     if (c->steps != 0) return fail(c, DBA_ESTATE, "dba_set_option: options are fixed once the first step is taken");
     if (value != value) return fail(c, DBA_EINVAL, "dba_set_option: the value is not a number");
     switch (option) {
-        case DBA_OPT_FUSED_LAUNCH: c->fused = value != 0.0 ? 1 : 0; return DBA_OK;
         case DBA_OPT_ADJUSTMENT: c->adjust = value != 0.0 ? 1 : 0; return DBA_OK;
         case DBA_OPT_NORMALIZE_FINISHED: c->normalize = value != 0.0 ? 1 : 0; return DBA_OK;
         case DBA_OPT_PRUNE_THRESHOLD: c->prune = value < 0.0 ? -1.0f : (float)value; return DBA_OK;

@@ -72,7 +72,6 @@ struct StepParams {
     u64 *rowlists;                    // [B*k,64] every row's best sums, decreasing, as selection-key bodies
     u64 *conskeys;                    // [B*k,64] selection keys (bank, score image, ~flat) of the
                                       //          row's expandable constraint tokens, 0 = none
-    unsigned int *counters;           // [B] rows of the sentence that have delivered their list
     // outputs (each may be null)
     int32_t *out_token, *out_backptr;
     float *out_score;
@@ -814,10 +813,8 @@ __device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kWavesPerBlock]
 
 // ROWS: beam rows per wave the code is laid out for (k <= 4 * ROWS): the loops over a wave's rows
 // are unrolled, so a smaller bound keeps the code of small beams short.
-// COHERENT: the row lists were written by other workgroups of the same launch and are read
-// with device-scope atomic loads (see dba_step_fused_kernel).
 // rowlists, conskeys, k: what the first loads need (p.rowlists, p.conskeys and p.k, handed over apart).
-template <int ROWS, bool COHERENT>
+template <int ROWS>
 __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowlists, const u64 *conskeys, int k,
                                             int b, MergeSmem &sm, u64 *cand)
 {
@@ -833,8 +830,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         rl[i] = 0;
         if (h < k) {
             const size_t o = ((size_t)b * k + h) * kWave + lane;
-            if (COHERENT) rl[i] = __hip_atomic_load(rowlists + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else rl[i] = rowlists[o];
+            rl[i] = rowlists[o];
         }
     }
 #pragma unroll
@@ -843,8 +839,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         ck[i] = 0;
         if (h < k) {
             const size_t o = ((size_t)b * k + h) * kWave + lane;
-            if (COHERENT) ck[i] = __hip_atomic_load(conskeys + o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else ck[i] = conskeys[o];
+            ck[i] = conskeys[o];
         }
     }
     __builtin_amdgcn_sched_barrier(0);

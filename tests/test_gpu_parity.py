@@ -300,29 +300,6 @@ def test_batch_equals_single_sentences(torch_gpu):
     assert fin[0].shape == (4, 12)
 
 
-@pytest.mark.parametrize("seed", [3, 6, 15])
-def test_one_launch_form_small(torch_gpu, seed):
-    """DBA_OPT_FUSED_LAUNCH: the one-launch form of the step gives the same results."""
-    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
-    k = [2, 13, 64][seed % 3]
-    wl = si.make_small(9100 + seed, 4, k, 1023, 10, max_phrases=5, max_len=4, dup_prob=0.35)
-    wl.eos_switch = 5
-    _harness().run_parity(wl, options={DBA_OPT_FUSED_LAUNCH: 1})
-
-
-def test_one_launch_form_config4(torch_gpu):
-    """The one-launch form at the headline shape: 1280 workgroups stream, 64 of them go on to merge
-    while others still stream (arrival counters, device-scope hand-over, wave priorities)."""
-    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
-    _harness().run_parity(si.make_config(4, T=16), options={DBA_OPT_FUSED_LAUNCH: 1}, check_state_every=4,
-                          progress="config4/one launch")
-
-
-def test_one_launch_form_config2(torch_gpu):
-    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
-    _harness().run_parity(si.make_config(2, T=15), options={DBA_OPT_FUSED_LAUNCH: 1})
-
-
 VARIANTS = [
     dict(adjust=False),
     dict(normalize=True),
@@ -437,13 +414,6 @@ def test_16bit_logp_config4(torch_gpu, fmt):
     _harness().run_parity(wl, logp_format=fmt, check_state_every=4, progress=f"config4 {fmt}")
 
 
-def test_16bit_logp_one_launch_form(torch_gpu):
-    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH
-    wl = si.make_small(9600, 3, 13, 1023, 10, max_phrases=5, max_len=4, dup_prob=0.35)
-    wl.eos_switch = 5
-    _harness().run_parity(wl, logp_format="bf16", options={DBA_OPT_FUSED_LAUNCH: 1})
-
-
 @pytest.mark.parametrize("k,V", [(64, 1 << 19), (2, 1 << 24)])
 def test_widest_coordinates(torch_gpu, k, V):
     """The limits of the key packing, bits(k-1) + bits(V-1) + bits(64) = 32: the widest beam with
@@ -553,7 +523,7 @@ def test_call_order_errors(torch_gpu):
     assert dba.dba_steps_done(ses.ctx) == 0
     ses.step(dev)
     with pytest.raises(dba.DbaError, match="first step"):
-        dba.dba_set_option(ses.ctx, dba.DBA_OPT_FUSED_LAUNCH, 1)
+        dba.dba_set_option(ses.ctx, dba.DBA_OPT_ADJUSTMENT, 0)
     mid = ses.finalize()                 # allowed after any number of steps
     assert mid[0].shape == (wl.B, 3)
     ses.step(dev)

@@ -32,21 +32,18 @@ def _decode(torch, wl, options=None, fmt=None):
     return trace
 
 
-@pytest.mark.parametrize("fused", [0, 1])
-def test_the_same_decode_twice_gives_the_same_bytes(fused):
+@pytest.mark.parametrize("paper_setup", [False, True])
+def test_the_same_decode_twice_gives_the_same_bytes(paper_setup):
     """Config-3 shapes (16 sentences, k = 10, V = 32000; boosted constraint tokens, so phrases start
-    and break), 40 steps with end-of-sentence from step 25, in both launch forms; and the two forms
-    agree with each other."""
+    and break), 40 steps with end-of-sentence from step 25, bare and with the options of Sec. 4 on."""
     import torch
-    from paper_1804_06609_amd import DBA_OPT_FUSED_LAUNCH, DBA_OPT_NORMALIZE_FINISHED, DBA_OPT_PRUNE_THRESHOLD
+    from paper_1804_06609_amd import DBA_OPT_NORMALIZE_FINISHED, DBA_OPT_PRUNE_THRESHOLD, DBA_OPT_TRACK_COMPLETED
     wl = si.make_config(3, T=40)
     wl.eos_switch = 25
-    opts = {DBA_OPT_FUSED_LAUNCH: fused, DBA_OPT_NORMALIZE_FINISHED: 1, DBA_OPT_PRUNE_THRESHOLD: 20.0}
+    opts = {DBA_OPT_NORMALIZE_FINISHED: 1, DBA_OPT_PRUNE_THRESHOLD: 20.0, DBA_OPT_TRACK_COMPLETED: 1} if paper_setup else None
     first = _decode(torch, wl, opts)
     second = _decode(torch, wl, opts)
     assert first == second
-    other = _decode(torch, wl, {**opts, DBA_OPT_FUSED_LAUNCH: 1 - fused})
-    assert first == other
 
 
 def test_the_same_bf16_decode_twice_gives_the_same_bytes():
@@ -87,7 +84,7 @@ def test_a_decode_writes_only_inside_its_buffers(case):
 def guarded_decode(case):
     """Workspace and the four output arrays sit between guard bands; after decodes with the widest beam
     and the most constraint tokens (k = 64, 64 tokens), with rows of odd length (unaligned rows, ragged
-    tiles) in fp32 and bf16, in both launch forms and with the options of Sec. 4 on, every guard byte is
+    tiles) in fp32 and bf16, bare and with the options of Sec. 4 on, every guard byte is
     as it was, and the outputs agree with an unguarded run."""
     import torch
     import paper_1804_06609_amd as dba
@@ -104,12 +101,14 @@ def guarded_decode(case):
     toks, poff, soff = wl.csr()
     B, k, V, T = wl.B, wl.k, wl.V, wl.T
     stream = torch.cuda.current_stream()
-    for fused in ((0,) if case == "noalloc" else (0, 1)):
+    for options in ({}, {dba.DBA_OPT_NORMALIZE_FINISHED: 1, dba.DBA_OPT_PRUNE_THRESHOLD: 20.0,
+                         dba.DBA_OPT_TRACK_COMPLETED: 1}):
         ws = _Guarded(torch, dba.dba_workspace_bytes(B, k, V, T, dba.DBA_MAX_CONS_TOKENS))
         o_tok, o_bp, o_sc = (_Guarded(torch, B * k * 4, align=4) for _ in range(3))
         o_fl = _Guarded(torch, B * k, align=1)
         ctx = dba.dba_init(B, k, V, T, wl.eos_id, wl.pad_id, toks, poff, soff, ws.ptr, ws.nbytes, stream.cuda_stream)
-        dba.dba_set_option(ctx, dba.DBA_OPT_FUSED_LAUNCH, fused)
+        for opt, val in options.items():
+            dba.dba_set_option(ctx, opt, val)
         got = []
         for t in range(T):
             lp = wl.logp(t)
@@ -130,12 +129,13 @@ def guarded_decode(case):
         dba.dba_finalize(ctx, *fin)
         dba.dba_destroy(ctx)
         for g in (ws, o_tok, o_bp, o_sc, o_fl):
-            assert g.guards_intact(), (case, fused)
-        # the unguarded run's trace holds, per step, the four outputs first
-        per_step = len(want[:-4]) // T
-        for t in range(T):
-            assert got[4 * t:4 * t + 4] == want[per_step * t:per_step * t + 4], (case, fused, t)
-        assert [a.tobytes() for a in fin] == want[-4:]
+            assert g.guards_intact(), (case, options)
+        if not options:
+            # the unguarded run's trace holds, per step, the four outputs first
+            per_step = len(want[:-4]) // T
+            for t in range(T):
+                assert got[4 * t:4 * t + 4] == want[per_step * t:per_step * t + 4], (case, t)
+            assert [a.tobytes() for a in fin] == want[-4:]
 
 
 def test_a_decode_replayed_from_a_hip_graph_matches_eager_launches():
