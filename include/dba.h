@@ -203,7 +203,7 @@ DBA_API int dba_get_state(dba_ctx *ctx, float *score_host, uint64_t *met_mask_ho
  *                               non-zero: every step remembers, per sentence, the best completed
  *                               hypothesis seen on any beam so far - ranked by score per word, a tie
  *                               keeps the earliest step, then the lowest slot - and dba_finalize
- *                               returns it (Sec. 3.3: the highest-scoring completed item is returned).
+ *                               returns it (Sec. 3.3: the answer is the best-scoring finished hypothesis).
  */
 #define DBA_OPT_ADJUSTMENT 2
 #define DBA_OPT_NORMALIZE_FINISHED 3

@@ -48,8 +48,8 @@
  * hypothesis completes; the pruning cut-off is the fp32 difference best -
  * threshold and a score equal to it survives.
  *
- * Completed hypotheses that leave the beam (Sec. 3.3: the highest-scoring
- * completed item is returned).  A completed hypothesis sits in the topmost
+ * Completed hypotheses that leave the beam (Sec. 3.3: what decoding returns is
+ * the best-scoring hypothesis among the finished ones).  A completed hypothesis sits in the topmost
  * bank and can lose its slot there to candidates with higher sums.  Reading
  * of the bare algorithm (dba_oracle_finalize): only the final beam is
  * searched, so such a hypothesis is forgotten.  Variant
@@ -511,8 +511,8 @@ int dba_oracle_step(int k, int V, int eos_id, int pad_id, int P, const int32_t *
 }
 
 /*
- * End of decoding for one sentence (Sec. 3.3: the highest-scoring completed
- * hypothesis is returned; Sec. 4: completed hypotheses are ranked by the
+ * End of decoding for one sentence (Sec. 3.3: the answer is the best-scoring
+ * finished hypothesis; Sec. 4: completed hypotheses are ranked by the
  * cumulative score divided by the number of words).
  * Reading: a hypothesis is completed when it has generated end-of-sentence
  * (which implies all constraints met); the length counts that token; the

@@ -82,8 +82,8 @@ struct StepParams {
     struct BestCompleted *best;       // [B] the record kept under `track`
 };
 
-// The best completed hypothesis a sentence has had on any of its beams so far (Sec. 3.3 returns the
-// highest-scoring completed item; Sec. 4 ranks completed hypotheses by score per word).
+// The best completed hypothesis a sentence has had on any of its beams so far (Sec. 3.3: the answer is
+// the best-scoring finished hypothesis; Sec. 4 ranks completed hypotheses by score per word).
 struct __attribute__((aligned(32))) BestCompleted {
     int have;          // 0: nothing completed yet
     int step, slot;    // where it was first seen: the beam after step `step`, place `slot`
