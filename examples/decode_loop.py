@@ -38,7 +38,8 @@ def main():
     wl.eos_switch = N // 3                       # the stand-in decoder starts to like end-of-sentence here
     toks, poff, soff = wl.csr()
     ses = Session(B, k, V, N, wl.eos_id, wl.pad_id, toks, poff, soff, options={
-        dba.DBA_OPT_NORMALIZE_FINISHED: 1, dba.DBA_OPT_PRUNE_THRESHOLD: 20.0})
+        dba.DBA_OPT_NORMALIZE_FINISHED: 1, dba.DBA_OPT_PRUNE_THRESHOLD: 20.0,
+        dba.DBA_OPT_TRACK_COMPLETED: 1})         # Sec. 3.3: the best completed hypothesis, also if it has left the beam
 
     steps = 0
     for t in range(N):                           # Alg. 1: for time step t in 1..N

@@ -6,11 +6,13 @@
 //                 exact top-k of the row (which holds the row's best token
 //                 and its share of the sentence's top-k) written as one sorted
 //                 64-key list per row - plus the row's expandable constraint
-//                 tokens (Alg. 2 inner loop): which they are, their sums, and the
-//                 bank each would land in, as selection keys;
-//   merge phase   one workgroup per sentence: sentence top-k from the row
-//                 lists, state transition add(), dedup, banks, allocation
-//                 with adjustment, selection, new beam.
+//                 tokens (Alg. 2 inner loop): which they are and their sums;
+//                 every key of either kind carries the bank it would land in
+//                 (the constraints met after add(), Sec. 3.1): selection keys;
+//   merge phase   one workgroup per sentence: the bar of the sentence's top-k
+//                 from the row lists, dedup, bank counts, allocation with
+//                 adjustment, selection, the state transition add() in full
+//                 for the winners, new beam.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <math.h>
