@@ -289,6 +289,26 @@ def test_most_candidates(torch_gpu):
     _harness().run_parity(wl)
 
 
+@pytest.mark.parametrize("k,fmt", [(8, None), (33, None), (13, "bf16")])
+def test_first_tokens_that_share_a_table_bucket(torch_gpu, k, fmt):
+    """The device looks a token's phrases up in a table bucketed by the low six bits of the first token.
+    Here phrases of one sentence begin with tokens that agree in those bits (70, 134, 198, 262), some
+    begin with the very same token, some tokens of that bucket begin no phrase (326), and all of them are
+    boosted so that they sit among the rows' best sums: the banks worked out at the end of a row and the
+    state transition of the winners must take the one-by-one path through the bucket."""
+    B, V, T = 4, 600, 14
+    cons = [
+        [[70, 5], [134], [198, 9, 10], [70, 6], [262, 134]],
+        [[134, 70], [198], [134, 70, 11]],
+        [[262], [70], [326 + 64, 70]],
+        [[70, 134, 198], [134, 198], [198]],
+    ]
+    wl = si.Workload(B=B, k=k, V=V, T=T, seed=4300 + k, constraints=cons,
+                     boost_tokens=[[70, 134, 198, 262, 326, 390] for _ in range(B)], boost_prob=0.6, boost_value=7.0)
+    wl.eos_switch = 9
+    _harness().run_parity(wl, logp_format=fmt)
+
+
 def test_batch_equals_single_sentences(torch_gpu):
     """Sentences never interact: a batch run equals one-sentence runs of the same rows."""
     h = _harness()
