@@ -21,8 +21,8 @@
  *     aborts.  dba_last_error gives the text of the last failure.
  *   - One ctx is used from one host thread at a time.
  *
- * Limits (checked by dba_init): 1 <= k <= 64; constraint tokens per sentence
- * <= 64; V <= 2^24; bits(k-1) + bits(V-1) + bits(Cmax) <= 32, where bits(x) is
+ * Limits (checked by dba_init): B <= 65535; 1 <= k <= 64; constraint tokens per
+ * sentence <= 64; V <= 2^24; bits(k-1) + bits(V-1) + bits(Cmax) <= 32, where bits(x) is
  * the width of x and Cmax the largest constraint-token count of a sentence
  * (e.g. k = 64, 64 tokens: V <= 2^19; k = 20, 32 tokens: V <= 2^21).
  */
@@ -78,7 +78,7 @@ DBA_API size_t dba_workspace_bytes(int B, int k, int V, int N, int max_cons_toke
  *
  * The initial beam of every sentence is one live, empty hypothesis in slot 0
  * with score +0.0; the other k-1 slots are empty.
- * Errors: DBA_EINVAL for sizes < 1, k > 64, k > V, ids outside [0,V),
+ * Errors: DBA_EINVAL for sizes < 1, B > 65535, k > 64, k > V, ids outside [0,V),
  * eos_id == pad_id, a constraint token equal to eos_id or pad_id, an empty
  * phrase, offsets not starting at 0 / not non-decreasing, more than 64 tokens
  * in a sentence, the width limit above, a misaligned workspace;

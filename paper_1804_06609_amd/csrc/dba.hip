@@ -502,7 +502,7 @@ static int init_impl(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     *out = nullptr;
     if (!shape_ok(B, k, V, N, 0))
         return fail(nullptr, DBA_EINVAL,
-                    "dba_init: need B,V,N >= 1 and 1 <= k <= %d, k <= V (got B=%d k=%d V=%d N=%d)",
+                    "dba_init: need 1 <= B <= 65535, V,N >= 1 and 1 <= k <= %d, k <= V (got B=%d k=%d V=%d N=%d)",
                     DBA_MAX_BEAM, B, k, V, N);
     if (eos_id < 0 || eos_id >= V || pad_id < 0 || pad_id >= V || eos_id == pad_id)
         return fail(nullptr, DBA_EINVAL, "dba_init: eos_id/pad_id must be distinct ids in [0,V)");
