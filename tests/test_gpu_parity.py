@@ -345,6 +345,27 @@ def test_variants_small(torch_gpu, seed, vi):
     _harness().run_parity(wl, **VARIANTS[vi])
 
 
+@pytest.mark.parametrize("block", range(6))
+def test_option_combinations_fuzz(torch_gpu, block):
+    """Sixty small decodes in which everything varies at once: shape (k = 1..64, V = 37..9001), phrase
+    count and length, repeated tokens, when end-of-sentence becomes likely, the element type of the
+    log-probs, and every combination of the options (adjustment, per-word scores, pruning threshold,
+    record of completed hypotheses)."""
+    for seed in range(10 * block, 10 * block + 10):
+        rs = si.Stream(seed, 77)
+        B = rs.randint(1, 6)
+        k = [1, 2, 3, 5, 8, 13, 20, 33, 64][seed % 9]
+        V = max(k + 3, [37, 64, 130, 257, 700, 1001, 1023, 2050, 4099, 9001][(seed // 3) % 10])
+        T = rs.randint(6, 16)
+        wl = si.make_small(20000 + seed, B, k, V, T, max_phrases=rs.randint(1, 8), max_len=rs.randint(1, 5),
+                           dup_prob=[0.0, 0.35, 0.7][seed % 3])
+        wl.eos_switch = rs.randint(2, T)
+        wl.eos_high = [0.5, 2.0, 3.0][seed % 3]
+        _harness().run_parity(wl, adjust=bool(seed & 1), normalize=bool(seed & 2),
+                              prune=[None, 20.0, 2.0, 0.0][(seed >> 2) & 3], track=bool(seed & 16),
+                              logp_format=[None, None, "bf16", "f16"][(seed >> 5) & 3])
+
+
 def test_paper_setup_config2(torch_gpu):
     """Config 2 shapes with the decoding set-up of Sec. 4: score per word for completed
     hypotheses, pruning threshold 20; end-of-sentence becomes likely after a third of the run."""
