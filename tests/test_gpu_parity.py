@@ -363,7 +363,7 @@ def test_option_combinations_fuzz(torch_gpu, block):
         wl.eos_high = [0.5, 2.0, 3.0][seed % 3]
         _harness().run_parity(wl, adjust=bool(seed & 1), normalize=bool(seed & 2),
                               prune=[None, 20.0, 2.0, 0.0][(seed >> 2) & 3], track=bool(seed & 16),
-                              logp_format=[None, None, "bf16", "f16"][(seed >> 5) & 3])
+                              logp_format=[None, None, "bf16", "f16"][(seed // 2) % 4])
 
 
 def test_paper_setup_config2(torch_gpu):
