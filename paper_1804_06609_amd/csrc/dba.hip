@@ -24,7 +24,7 @@ using namespace dba;
 // logp, V, k, first_step are what the first loads need; the kernels take them as leading scalar
 // arguments, which the hardware hands over in registers at wave start (kernel-argument preload),
 // so that the first two tiles are requested before any argument has been read from memory.
-template <int U, int FMT>
+template <int U, int FMT, int NW>
 __device__ __forceinline__ void stream_phase(const StepParams &p, const void *logp, int V, int k, int first_step,
                                              int b, int h, StreamSmem &sm)
 {
@@ -32,7 +32,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, const void *lo
     const int row = b * k + h;
     const int lane = lane_id();
     const int wave = (int)(threadIdx.x >> 6);
-    constexpr int nwaves = kWavesPerBlock;
+    constexpr int nwaves = NW;
     const bool gatherer = wave == nwaves - 1;     // this wave also fetches the constraint tokens
 
     // the first two tiles of the row are requested before anything else: they need nothing of
@@ -133,11 +133,11 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, const void *lo
 
 // First launch of a step.  Grid: (k, B) workgroups of 256 threads, one per beam row, in row
 // order.  k_first = k | first_step << 16.
-template <int U, int FMT>
-__global__ __launch_bounds__(kBlock) void dba_stream_kernel(const void *logp, int V, int k_first, const StepParams p)
+template <int U, int FMT, int NW>
+__global__ __launch_bounds__(NW * kWave) void dba_stream_kernel(const void *logp, int V, int k_first, const StepParams p)
 {
     __shared__ StreamSmem sm;
-    stream_phase<U, FMT>(p, logp, V, k_first & 0xFFFF, k_first >> 16, (int)blockIdx.y, (int)blockIdx.x, sm);
+    stream_phase<U, FMT, NW>(p, logp, V, k_first & 0xFFFF, k_first >> 16, (int)blockIdx.y, (int)blockIdx.x, sm);
 }
 
 // Second launch of a step: the merge phase.  Grid: one workgroup per sentence.  The pointers to the row lists and the beam width
@@ -726,10 +726,27 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
     // the merge phase is compiled for 4, 8 and 16 beam rows per wave: the smallest that holds k
     const int rows = c->k <= 16 ? 4 : (c->k <= 32 ? 8 : 16);
     {
-        switch (logp_format) {
-            case DBA_LOGP_F16: dba_stream_kernel<kTileLoads, kFmtF16><<<grid, block, 0, c->stream>>>(p.logp, p.V, kf, p); break;
-            case DBA_LOGP_BF16: dba_stream_kernel<kTileLoads, kFmtBF16><<<grid, block, 0, c->stream>>>(p.logp, p.V, kf, p); break;
-            default: dba_stream_kernel<kTileLoads, kFmtF32><<<grid, block, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+        // Waves per beam row (measured on MI355X, fp32 and 16-bit inputs, 10 to 8192 rows): eight where the
+        // grid cannot fill the chip by itself (at most two rows per compute unit) and a row has work for
+        // them, and where rows are long (from 160 KB on: the floor then rests on a larger share of the
+        // row and fewer sums are looked at closely); four otherwise - with rows of 64-128 KB and
+        // thousands of them, twice the workgroups per compute unit stream faster than twice the waves.
+        const size_t row_bytes = (size_t)c->V * elem;
+        const int stream_waves =
+            (((size_t)c->B * c->k <= 512 && row_bytes >= 32768) || row_bytes >= 163840) ? 8 : 4;
+        const dim3 sblock((unsigned)(stream_waves * kWave));
+        if (stream_waves == 8) {
+            switch (logp_format) {
+                case DBA_LOGP_F16: dba_stream_kernel<kTileLoads, kFmtF16, 8><<<grid, sblock, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+                case DBA_LOGP_BF16: dba_stream_kernel<kTileLoads, kFmtBF16, 8><<<grid, sblock, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+                default: dba_stream_kernel<kTileLoads, kFmtF32, 8><<<grid, sblock, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+            }
+        } else {
+            switch (logp_format) {
+                case DBA_LOGP_F16: dba_stream_kernel<kTileLoads, kFmtF16, 4><<<grid, sblock, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+                case DBA_LOGP_BF16: dba_stream_kernel<kTileLoads, kFmtBF16, 4><<<grid, sblock, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+                default: dba_stream_kernel<kTileLoads, kFmtF32, 4><<<grid, sblock, 0, c->stream>>>(p.logp, p.V, kf, p); break;
+            }
         }
         const dim3 mgrid((unsigned)c->B);
         if (rows == 4) dba_merge_kernel<4><<<mgrid, block, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);

@@ -26,6 +26,7 @@ constexpr int kMaxBeam = 64;
 constexpr int kMaxCons = 64;          // constraint tokens (and phrases) per sentence
 constexpr int kBlock = 256;           // threads per workgroup
 constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kStreamWaves = 8;       // most waves a stream-phase workgroup (one beam row) can have: 4 or 8 are used
 constexpr int kTileLoads = 4;         // 16-byte loads per lane and tile in the stream phase
 constexpr int kFmtF32 = 0;            // element type of the log-probs: fp32,
 constexpr int kFmtF16 = 1;            // IEEE binary16,
@@ -381,11 +382,11 @@ __device__ __forceinline__ void block_eos(typename Logp<FMT>::vec_t (&x)[U], int
 
 // LDS shared by the waves of one row's workgroup during the stream phase.
 struct StreamSmem {
-    u64 wl[kWavesPerBlock][kWave];      // the waves' lists, for the final merge
-    u64 stage[kWavesPerBlock][kStageCap];   // candidates parked between flushes
-    uint32_t boot[kWavesPerBlock][kWave];   // sorted per-lane maxima of every wave's first tile (order images)
-    int parked[kWavesPerBlock];         // end of the row: keys each wave has left in its stage,
-    int has_list[kWavesPerBlock];       // and whether it holds a list from earlier folds
+    u64 wl[kStreamWaves][kWave];        // the waves' lists, for the final merge
+    u64 stage[kStreamWaves][kStageCap]; // candidates parked between flushes
+    uint32_t boot[kStreamWaves][kWave]; // sorted per-lane maxima of every wave's first tile (order images)
+    int parked[kStreamWaves];           // end of the row: keys each wave has left in its stage,
+    int has_list[kStreamWaves];         // and whether it holds a list from earlier folds
 };
 
 // One wave's share of one row: tiles wave, wave+nwaves, ... of 64*U groups of 16 bytes each.
@@ -555,18 +556,16 @@ __device__ __forceinline__ u64 finish_row(StreamSmem &sm, u64 list, int parked, 
         sm.has_list[wave] = mine_has ? 1 : 0;
     }
     __syncthreads();
-    int n1 = sm.parked[0], n2 = n1, n3 = n1, n = n1, any = sm.has_list[0];
-    if (nwaves > 1) {
-        n2 = n1 + sm.parked[1];
-        n3 = n2;
-        n = n2;
-        any |= sm.has_list[1];
+    // keys parked by waves 0..w-1 (pre[w]); all of them (n)
+    int pre[kStreamWaves + 1];
+    int any = 0;
+    pre[0] = 0;
+#pragma unroll
+    for (int w = 0; w < kStreamWaves; ++w) {
+        pre[w + 1] = pre[w] + (w < nwaves ? sm.parked[w] : 0);
+        any |= w < nwaves ? sm.has_list[w] : 0;
     }
-    if (nwaves > 2) {
-        n3 = n2 + sm.parked[2];
-        n = n3 + sm.parked[3];
-        any |= sm.has_list[2] | sm.has_list[3];
-    }
+    const int n = pre[kStreamWaves];
     const int nchunks = (n + kWave - 1) >> 6;
     u64 part = 0;
     bool have = false;
@@ -574,8 +573,13 @@ __device__ __forceinline__ u64 finish_row(StreamSmem &sm, u64 list, int parked, 
         const int i = c * kWave + lane;
         u64 key = 0;
         if (i < n) {
-            const int w = (i >= n1 ? 1 : 0) + (i >= n2 ? 1 : 0) + (i >= n3 ? 1 : 0);
-            const int first = w == 0 ? 0 : (w == 1 ? n1 : (w == 2 ? n2 : n3));
+            int w = 0, first = 0;
+#pragma unroll
+            for (int j = 1; j < kStreamWaves; ++j)
+                if (i >= pre[j]) {
+                    w = j;
+                    first = pre[j];
+                }
             key = sm.stage[w][i - first];
         }
         const u64 sorted = sort64_desc<u64, true>(key);
