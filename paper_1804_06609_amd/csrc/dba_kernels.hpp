@@ -474,8 +474,16 @@ __device__ __forceinline__ int RowStream<U, FMT>::run(float prev, int eos_block,
     if (nwaves > 1) {
         sm.boot[wave][lane] = boot;
         __syncthreads();
-        for (int w = 0; w < nwaves; ++w)
-            if (w != wave) boot = merge_desc<uint32_t>(boot, sm.boot[w][lane]);
+        const int share = kWave / nwaves;              // entries of every wave's list that fit one 64-lane sort
+        if (kk <= 3 * share) {
+            // Any k values that different lanes hold give a valid floor, so the best `share` of every
+            // wave's list, sorted once, do: the k-th of them is the k-th of all unless one wave
+            // holds more than `share` of the k greatest (then it is a little lower, never wrong).
+            boot = sort64_desc<uint32_t>(sm.boot[lane / share][lane % share]);
+        } else {
+            for (int w = 0; w < nwaves; ++w)
+                if (w != wave) boot = merge_desc<uint32_t>(boot, sm.boot[w][lane]);
+        }
     }
     st.floor = float_from_ord((uint32_t)__builtin_amdgcn_readlane((int)boot, kk - 1));
     st.thr = fmaxf(st.floor, kLowestFinite);
