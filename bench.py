@@ -37,8 +37,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled against a plain copy), and
 # the digest of the kernel sources those counters were taken with: the line carries the figure only
 # while the sources are still those, null otherwise.
-TRAFFIC_BYTES_PER_LAUNCH = 168784637
-TRAFFIC_KERNEL_SHA16 = "f2deef709be200f7"
+TRAFFIC_BYTES_PER_LAUNCH = 168780798
+TRAFFIC_KERNEL_SHA16 = "ed0148b4316cf6bd"
 
 
 def kernel_sources_sha16() -> str:
