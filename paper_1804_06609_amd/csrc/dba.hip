@@ -719,8 +719,8 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
     p.all_finished = at<uint8_t>(c, L.all_finished);
     p.best = at<BestCompleted>(c, L.best);
 
-    // 4 wavefronts per row, 4 loads of 16 bytes per lane and tile: 1280 rows x 4 waves fill the 1024 SIMDs
-    // five deep with two 4 KB tiles in flight per wave (measured best on MI355X at V = 32000)
+    // one workgroup per beam row, 4 loads of 16 bytes per lane and tile, two 4 KB tiles in flight per wave: at
+    // 1280 rows of four waves the 1024 SIMDs are filled five deep (measured best on MI355X at V = 32000)
     const dim3 grid((unsigned)c->k, (unsigned)c->B), block(kBlock);      // row order: slot fastest
     const int kf = p.k | (p.first_step << 16);
     // the merge phase is compiled for 4, 8 and 16 beam rows per wave: the smallest that holds k
