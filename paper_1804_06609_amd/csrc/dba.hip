@@ -18,7 +18,7 @@ using namespace dba;
 // ---------------------------------------------------------------------------
 // kernels
 // ---------------------------------------------------------------------------
-// Stream phase of one beam row (sentence b, slot h) by one workgroup of four waves: leaves the row's
+// Stream phase of one beam row (sentence b, slot h) by one workgroup of NW waves: leaves the row's
 // sorted top keys in p.rowlists and the keys of its constraint tokens in p.conskeys.
 // U = 16-byte loads each lane keeps in flight per tile; FMT = element type of the log-probs.
 // logp, V, k, first_step are what the first loads need; the kernels take them as leading scalar
@@ -131,7 +131,7 @@ __device__ __forceinline__ void stream_phase(const StepParams &p, const void *lo
     }
 }
 
-// First launch of a step.  Grid: (k, B) workgroups of 256 threads, one per beam row, in row
+// First launch of a step.  Grid: (k, B) workgroups of NW waves, one per beam row, in row
 // order.  k_first = k | first_step << 16.
 template <int U, int FMT, int NW>
 __global__ __launch_bounds__(NW * kWave) void dba_stream_kernel(const void *logp, int V, int k_first, const StepParams p)
@@ -140,15 +140,16 @@ __global__ __launch_bounds__(NW * kWave) void dba_stream_kernel(const void *logp
     stream_phase<U, FMT, NW>(p, logp, V, k_first & 0xFFFF, k_first >> 16, (int)blockIdx.y, (int)blockIdx.x, sm);
 }
 
-// Second launch of a step: the merge phase.  Grid: one workgroup per sentence.  The pointers to the row lists and the beam width
+// Second launch of a step: the merge phase.  Grid: one workgroup of MW waves per sentence, each wave
+// taking up to ROWS beam rows (k <= ROWS * MW).  The pointers to the row lists and the beam width
 // come first: they are all the first loads need.
-template <int ROWS>
-__global__ __launch_bounds__(kBlock) void dba_merge_kernel(const u64 *rowlists, const u64 *conskeys, int k,
-                                                           const StepParams p)
+template <int ROWS, int MW>
+__global__ __launch_bounds__(MW * kWave) void dba_merge_kernel(const u64 *rowlists, const u64 *conskeys, int k,
+                                                               const StepParams p)
 {
     extern __shared__ __align__(16) unsigned char dyn_smem[];
     __shared__ MergeSmem sm;
-    merge_phase<ROWS>(p, rowlists, conskeys, k, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
+    merge_phase<ROWS, MW>(p, rowlists, conskeys, k, (int)blockIdx.x, sm, reinterpret_cast<u64 *>(dyn_smem));
 }
 
 // Reference read: the largest element of each row, one workgroup per row, with the tile order and
@@ -721,10 +722,8 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
 
     // one workgroup per beam row, 4 loads of 16 bytes per lane and tile, two 4 KB tiles in flight per wave: at
     // 1280 rows of four waves the 1024 SIMDs are filled five deep (measured best on MI355X at V = 32000)
-    const dim3 grid((unsigned)c->k, (unsigned)c->B), block(kBlock);      // row order: slot fastest
+    const dim3 grid((unsigned)c->k, (unsigned)c->B);      // row order: slot fastest
     const int kf = p.k | (p.first_step << 16);
-    // the merge phase is compiled for 4, 8 and 16 beam rows per wave: the smallest that holds k
-    const int rows = c->k <= 16 ? 4 : (c->k <= 32 ? 8 : 16);
     {
         // Waves per beam row (measured on MI355X, fp32 and 16-bit inputs, 10 to 8192 rows): eight where the
         // grid cannot fill the chip by itself (at most two rows per compute unit) and a row has work for
@@ -748,10 +747,17 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
                 default: dba_stream_kernel<kTileLoads, kFmtF32, 4><<<grid, sblock, 0, c->stream>>>(p.logp, p.V, kf, p); break;
             }
         }
+        // The merge phase is compiled for (rows per wave, waves): the beam rows of a sentence are dealt out to
+        // the waves of its workgroup.  Four waves of four rows up to k = 16; from there on eight waves (of four
+        // rows up to k = 32, of eight beyond): fewer lists per wave to merge and to scan, a wave of its own
+        // for every chunk of candidates, at the price of a deeper tree where the waves' lists are joined
+        // (measured on MI355X: 6.2 / 6.5 us with four / eight waves at k = 10, 7.7 / 7.4 at k = 20, 19.3 / 15.4
+        // at k = 64).
         const dim3 mgrid((unsigned)c->B);
-        if (rows == 4) dba_merge_kernel<4><<<mgrid, block, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
-        else if (rows == 8) dba_merge_kernel<8><<<mgrid, block, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
-        else dba_merge_kernel<16><<<mgrid, block, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+        const dim3 mblock8(8 * kWave), mblock4(4 * kWave);
+        if (c->k <= 16) dba_merge_kernel<4, 4><<<mgrid, mblock4, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+        else if (c->k <= 32) dba_merge_kernel<4, 8><<<mgrid, mblock8, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+        else dba_merge_kernel<8, 8><<<mgrid, mblock8, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_step: launch failed: %s", hipGetErrorString(e));

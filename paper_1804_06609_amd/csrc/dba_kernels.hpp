@@ -24,7 +24,7 @@ namespace dba {
 
 constexpr int kMaxBeam = 64;
 constexpr int kMaxCons = 64;          // constraint tokens (and phrases) per sentence
-constexpr int kBlock = 256;           // threads per workgroup
+constexpr int kBlock = 256;           // threads per workgroup of the small helper kernels
 constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kStreamWaves = 8;       // most waves a stream-phase workgroup (one beam row) can have: 4 or 8 are used
 constexpr int kTileLoads = 4;         // 16-byte loads per lane and tile in the stream phase
@@ -112,10 +112,12 @@ struct __attribute__((aligned(16))) HypState {
     int misc;      // finished flag | constraints met << 8
 };
 
+constexpr int kMergeWavesMax = 8;     // most waves a merge-phase workgroup (one sentence) can have: 4 or 8 are used
+
 struct MergeSmem {
-    uint32_t ws[kWavesPerBlock][kWave];      // every wave's best score images
-    uint32_t wf[kWavesPerBlock][kWave];      // and the greatest images its merges dropped
-    uint32_t ws2[kWavesPerBlock][kWave];     // every wave's best low words among tied keys
+    uint32_t ws[kMergeWavesMax][kWave];      // every wave's best score images
+    uint32_t wf[kMergeWavesMax][kWave];      // and the greatest images its merges dropped
+    uint32_t ws2[kMergeWavesMax][kWave];     // every wave's best low words among tied keys
     HypState hyp[kMaxBeam];
     u64 sel[kMaxBeam];
     ConsTab ct;
@@ -766,15 +768,15 @@ __device__ __forceinline__ int nmet_after(int nmet, int ip, int iq, bool is_next
 // chains of merges run side by side, so that their instructions interleave, and are joined at
 // the end.  A list whose head is below place `kth` of the chain it would join cannot change
 // places 0..kth of the result and may be skipped (LOOK); apart from that the result is exact.
-template <int R, bool LOOK, typename List>
+template <int R, int MW, bool LOOK, typename List>
 __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List list, uint32_t &fell)
 {
     uint32_t a0 = wave < k ? list(0) : 0u;
-    uint32_t a1 = (R > 1 && wave + kWavesPerBlock < k) ? list(R > 1 ? 1 : 0) : 0u;
+    uint32_t a1 = (R > 1 && wave + MW < k) ? list(R > 1 ? 1 : 0) : 0u;
 #pragma unroll
     for (int i = 2; i < R; i += 2) {
-        if (wave + i * kWavesPerBlock < k) {               // wave-uniform
-            const bool pair = i + 1 < R && wave + (i + 1) * kWavesPerBlock < k;
+        if (wave + i * MW < k) {               // wave-uniform
+            const bool pair = i + 1 < R && wave + (i + 1) * MW < k;
             const uint32_t s0 = list(i);
             const uint32_t s1 = pair ? list(i + 1 < R ? i + 1 : i) : 0u;
             // LOOK: lists are looked at before they are merged (worth it where many are empty or
@@ -798,37 +800,41 @@ __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List l
         }
     }
     if (LOOK) return __builtin_amdgcn_readlane((int)a1, 0) != 0 ? merge32_desc(a0, a1, fell) : a0;
-    return (R > 1 && wave + kWavesPerBlock < k) ? merge32_desc(a0, a1, fell) : a0;
+    return (R > 1 && wave + MW < k) ? merge32_desc(a0, a1, fell) : a0;
 }
 
-// The 64 greatest keys of the four waves' lists, in every wave (one barrier).  SPARSE: most
-// lists are expected to be empty, and an empty list costs nothing; otherwise two of the three
-// merges run side by side.
-template <bool SPARSE>
-__device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kWavesPerBlock][kWave], int wave, int lane,
+// The 64 greatest keys of all the waves' lists, in every wave (one barrier).  SPARSE: most
+// lists are expected to be empty, and an empty list costs nothing; otherwise the merges form a
+// tree whose independent pairs run side by side.
+template <int MW, bool SPARSE>
+__device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kMergeWavesMax][kWave], int wave, int lane,
                                                  uint32_t mine, uint32_t &fell)
 {
     buf[wave][lane] = mine;
     __syncthreads();
-    const uint32_t o1 = buf[(wave + 1) & (kWavesPerBlock - 1)][lane];
-    const uint32_t o2 = buf[(wave + 2) & (kWavesPerBlock - 1)][lane];
-    const uint32_t o3 = buf[(wave + 3) & (kWavesPerBlock - 1)][lane];
+    uint32_t o[MW];
+    o[0] = mine;
+#pragma unroll
+    for (int w = 1; w < MW; ++w) o[w] = buf[(wave + w) & (MW - 1)][lane];
     if (SPARSE) {
         uint32_t acc = mine;
-        if (__builtin_amdgcn_readlane((int)o1, 0) != 0) acc = merge32_desc(acc, o1, fell);
-        if (__builtin_amdgcn_readlane((int)o2, 0) != 0) acc = merge32_desc(acc, o2, fell);
-        if (__builtin_amdgcn_readlane((int)o3, 0) != 0) acc = merge32_desc(acc, o3, fell);
+#pragma unroll
+        for (int w = 1; w < MW; ++w)
+            if (__builtin_amdgcn_readlane((int)o[w], 0) != 0) acc = merge32_desc(acc, o[w], fell);
         return acc;
     }
-    const uint32_t x = merge32_desc(mine, o1, fell);
-    const uint32_t y = merge32_desc(o2, o3, fell);
-    return merge32_desc(x, y, fell);
+#pragma unroll
+    for (int span = 1; span < MW; span *= 2)
+#pragma unroll
+        for (int w = 0; w + span < MW; w += 2 * span) o[w] = merge32_desc(o[w], o[w + span], fell);
+    return o[0];
 }
 
-// ROWS: beam rows per wave the code is laid out for (k <= 4 * ROWS): the loops over a wave's rows
-// are unrolled, so a smaller bound keeps the code of small beams short.
+// MW: waves of the sentence's workgroup; ROWS: beam rows per wave the code is laid out for
+// (k <= MW * ROWS; wave w takes rows w, w + MW, ...): the loops over a wave's rows are unrolled, so a
+// smaller bound keeps the code of small beams short.
 // rowlists, conskeys, k: what the first loads need (p.rowlists, p.conskeys and p.k, handed over apart).
-template <int ROWS>
+template <int ROWS, int MW>
 __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowlists, const u64 *conskeys, int k,
                                             int b, MergeSmem &sm, u64 *cand)
 {
@@ -840,7 +846,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
     u64 rl[kRowsPerWave], ck[kRowsPerWave];
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) {
-        const int h = wave + i * kWavesPerBlock;
+        const int h = wave + i * MW;
         rl[i] = 0;
         if (h < k) {
             const size_t o = ((size_t)b * k + h) * kWave + lane;
@@ -849,7 +855,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
     }
 #pragma unroll
     for (int i = 0; i < kRowsPerWave; ++i) {
-        const int h = wave + i * kWavesPerBlock;
+        const int h = wave + i * MW;
         ck[i] = 0;
         if (h < k) {
             const size_t o = ((size_t)b * k + h) * kWave + lane;
@@ -891,7 +897,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
     // for the last places: the same merge over the low words (the coordinates, complemented)
     // of the keys with that score finds the last one that gets in. -------------------------
     uint32_t fell = 0;
-    uint32_t accs = wave_best64<kRowsPerWave, (kRowsPerWave > 8)>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
+    uint32_t accs = wave_best64<kRowsPerWave, MW, (kRowsPerWave > 4)>(wave, k, k - 1, [&](int i) { return (uint32_t)(rl[i] >> fb); }, fell);
     // the sentence's tables and beam go to LDS only now: their loads were issued after those of the
     // row lists and arrive later, and the merges above needed none of them
     if (tid <= kMaxCons) sm.ct.poff[tid] = ld_poff;
@@ -922,7 +928,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         sm.hyp[tid] = hs;
     }
     sm.wf[wave][lane] = fell;
-    accs = block_best64<false>(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
+    accs = block_best64<MW, false>(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
     const int C = sm.ct.poff[P];
     // every wave now holds the sentence's best score images, lane i = i-th best
     const uint32_t tau_s = (uint32_t)__builtin_amdgcn_readlane((int)accs, k - 1);
@@ -931,8 +937,8 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         settled = (int)__popcll(__ballot(accs >= tau_s)) == k;  // places k.. hold lower scores
         if (settled && k == kWave) {
             // every place is taken: a tie may hide among the keys the merges dropped
-            for (int w = 1; w < kWavesPerBlock; ++w) {
-                const uint32_t f = sm.wf[(wave + w) & (kWavesPerBlock - 1)][lane];
+            for (int w = 1; w < MW; ++w) {
+                const uint32_t f = sm.wf[(wave + w) & (MW - 1)][lane];
                 fell = fell > f ? fell : f;
             }
             settled = wave_max_u32(fell) < tau_s;
@@ -945,7 +951,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         const int need = k - __popcll(__ballot(accs > tau_s));      // places left for the tied keys
         const uint32_t low_bias = fb < 32 ? 1u : 0u;
         uint32_t unused = 0;
-        uint32_t accl = wave_best64<kRowsPerWave, true>(wave, k, need - 1, [&](int i) {
+        uint32_t accl = wave_best64<kRowsPerWave, MW, true>(wave, k, need - 1, [&](int i) {
             // the tied keys of a decreasing list are neighbours: move them to the front
             // (a low word may be 0 where it has fewer than 32 bits: one is added meanwhile)
             const uint32_t hi = (uint32_t)(rl[i] >> fb);
@@ -955,7 +961,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
             const uint32_t moved = (uint32_t)__shfl((int)lo, (lane + first) & (kWave - 1), kWave);
             return lane + first < kWave ? moved : 0u;
         }, unused);
-        accl = block_best64<true>(sm.ws2, wave, lane, accl, unused);
+        accl = block_best64<MW, true>(sm.ws2, wave, lane, accl, unused);
         const uint32_t tau_l = (uint32_t)__builtin_amdgcn_readlane((int)accl, need - 1);
         tau = ((u64)tau_s << fb) | (u64)(tau_l - low_bias);
     }
@@ -980,7 +986,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
     if (tau != 0) {
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
-            if (wave + i * kWavesPerBlock < k) {
+            if (wave + i * MW < k) {
                 const u64 best = read_lane(rl[i], 0) & body_mask;
                 gm |= ((rl[i] & body_mask) >= keep_from ? 1u : 0u) << i;
                 const u64 body = ck[i] & body_mask;
@@ -993,12 +999,12 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         // fewer than k finite sums: all of them are among the k best, none is left for source 2
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i)
-            if (wave + i * kWavesPerBlock < k) gm |= (rl[i] != 0 ? 1u : 0u) << i;
+            if (wave + i * MW < k) gm |= (rl[i] != 0 ? 1u : 0u) << i;
     }
     if (__ballot(some_tied)) {                             // rare
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
-            if (wave + i * kWavesPerBlock < k) {
+            if (wave + i * MW < k) {
                 const u64 body = ck[i] & body_mask;
                 u64 tied = __ballot(((cm >> i) & 1u) != 0 && body >= tau);
                 while (tied) {
@@ -1028,7 +1034,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         int to = at + g_incl - g;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
-            if (wave + i * kWavesPerBlock < k && ((gm >> i) & 1u)) {
+            if (wave + i * MW < k && ((gm >> i) & 1u)) {
                 cand[to++] = rl[i];
                 atomicAdd(&sm.cnt[mb ? (int)(rl[i] >> sel_shift) : 0], 1);    // bank = constraints met (Sec. 3.1)
             }
@@ -1036,7 +1042,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         to = at + n13_all + c_incl - c;
 #pragma unroll
         for (int i = 0; i < kRowsPerWave; ++i) {
-            if (wave + i * kWavesPerBlock < k && ((cm >> i) & 1u)) {
+            if (wave + i * MW < k && ((cm >> i) & 1u)) {
                 cand[to++] = ck[i];
                 atomicAdd(&sm.cnt[mb ? (int)(ck[i] >> sel_shift) : 0], 1);
             }
@@ -1065,13 +1071,13 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
     // chunks of 64 are sorted by one wave each (wave 0, busy with the allocation, last); a
     // candidate's rank is its place in its own chunk plus, by a search with three probes a round,
     // the keys greater than it in every other chunk ------------------------------------------------------------
-    const int my_first = kWavesPerBlock - 1 - wave;
-    for (int c = my_first; c < nchunks; c += kWavesPerBlock) {
+    const int my_first = MW - 1 - wave;
+    for (int c = my_first; c < nchunks; c += MW) {
         const int i = c * kWave + lane;
         cand[i] = sort64_desc<u64, true>(i < ncand ? cand[i] : 0ull);
     }
     __syncthreads();
-    for (int c = my_first; c < nchunks; c += kWavesPerBlock) {
+    for (int c = my_first; c < nchunks; c += MW) {
         const u64 mine = cand[c * kWave + lane];
         int rank = lane;
         // four searches at a time, so that their LDS reads overlap
@@ -1119,10 +1125,6 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         // keys greater than its own (at most 64 uniform LDS reads: cheaper than a 64-lane sort)
         const bool live = lane < nsel;
         const u64 mine = live ? sm.sel[lane] : 0ull;
-        int slot = 0;
-        for (int j = 0; j < nsel; j += 4)                 // (kMaxBeam is a multiple of 4; unused places hold 0)
-            slot += (sm.sel[j] > mine ? 1 : 0) + (sm.sel[j + 1] > mine ? 1 : 0) + (sm.sel[j + 2] > mine ? 1 : 0) +
-                    (sm.sel[j + 3] > mine ? 1 : 0);
         int token = p.pad_id, parent = -1, length = 0, ipq2 = -1, nxt2 = -1;
         float score = -INFINITY;
         u64 met2 = 0, inc2 = 0;
@@ -1182,6 +1184,10 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
             // division, the length counts end-of-sentence); it competed with its raw sum above
             if (p.normalize && fin2 && !pfin) score = __fdiv_rn(score, (float)length);
         }
+        int slot = 0;
+        for (int j = 0; j < nsel; j += 4)                 // (kMaxBeam is a multiple of 4; unused places hold 0)
+            slot += (sm.sel[j] > mine ? 1 : 0) + (sm.sel[j + 1] > mine ? 1 : 0) + (sm.sel[j + 2] > mine ? 1 : 0) +
+                    (sm.sel[j + 3] > mine ? 1 : 0);
         // Sec. 4 / Sec. 6.3: hypotheses, completed or not, below (best completed - threshold) leave
         // the beam; the others close ranks
         bool keep = live;
