@@ -127,6 +127,8 @@ struct MergeSmem {
     int cnt[2 * kMaxCons];
     int alloc[2 * kMaxCons];
     int start[2 * kMaxCons];
+    uint32_t bar_score;               // with eight waves: the score image of the bar of the k best, from the waves that join the lists,
+    int bar_need;                     // and the places left for keys that tie at that score (-1: no tie to settle)
     int ncand;
     int nsel;
     u64 kept;                         // pruning: bit i = the hypothesis at place i of the new beam stays
@@ -803,31 +805,37 @@ __device__ __forceinline__ uint32_t wave_best64(int wave, int k, int kth, List l
     return (R > 1 && wave + MW < k) ? merge32_desc(a0, a1, fell) : a0;
 }
 
-// The 64 greatest keys of all the waves' lists, in every wave (one barrier).  SPARSE: most
-// lists are expected to be empty, and an empty list costs nothing; otherwise the merges form a
-// tree whose independent pairs run side by side.
-template <int MW, bool SPARSE>
-__device__ __forceinline__ uint32_t block_best64(uint32_t (&buf)[kMergeWavesMax][kWave], int wave, int lane,
-                                                 uint32_t mine, uint32_t &fell)
+// The 64 greatest keys of the lists the MW waves have left in buf (after a barrier), for the
+// calling wave: a tree of merges whose independent pairs run side by side.
+template <int MW>
+__device__ __forceinline__ uint32_t join_best64(const uint32_t (&buf)[kMergeWavesMax][kWave], int wave, int lane,
+                                                uint32_t &fell)
 {
-    buf[wave][lane] = mine;
-    __syncthreads();
     uint32_t o[MW];
-    o[0] = mine;
 #pragma unroll
-    for (int w = 1; w < MW; ++w) o[w] = buf[(wave + w) & (MW - 1)][lane];
-    if (SPARSE) {
-        uint32_t acc = mine;
-#pragma unroll
-        for (int w = 1; w < MW; ++w)
-            if (__builtin_amdgcn_readlane((int)o[w], 0) != 0) acc = merge32_desc(acc, o[w], fell);
-        return acc;
-    }
+    for (int w = 0; w < MW; ++w) o[w] = buf[(wave + w) & (MW - 1)][lane];
 #pragma unroll
     for (int span = 1; span < MW; span *= 2)
 #pragma unroll
         for (int w = 0; w + span < MW; w += 2 * span) o[w] = merge32_desc(o[w], o[w + span], fell);
     return o[0];
+}
+
+// The same where most lists are expected to be empty (an empty list costs nothing), in every
+// wave; one barrier.
+template <int MW>
+__device__ __forceinline__ uint32_t block_best64_sparse(uint32_t (&buf)[kMergeWavesMax][kWave], int wave, int lane,
+                                                        uint32_t mine, uint32_t &fell)
+{
+    buf[wave][lane] = mine;
+    __syncthreads();
+    uint32_t acc = mine;
+#pragma unroll
+    for (int w = 1; w < MW; ++w) {
+        const uint32_t other = buf[(wave + w) & (MW - 1)][lane];
+        if (__builtin_amdgcn_readlane((int)other, 0) != 0) acc = merge32_desc(acc, other, fell);
+    }
+    return acc;
 }
 
 // MW: waves of the sentence's workgroup; ROWS: beam rows per wave the code is laid out for
@@ -928,27 +936,46 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
         sm.hyp[tid] = hs;
     }
     sm.wf[wave][lane] = fell;
-    accs = block_best64<MW, false>(sm.ws, wave, lane, accs, fell);    // barrier: tables and beam are in LDS too
+    sm.ws[wave][lane] = accs;
+    __syncthreads();                                       // tables and beam are in LDS too
     const int C = sm.ct.poff[P];
-    // every wave now holds the sentence's best score images, lane i = i-th best
-    const uint32_t tau_s = (uint32_t)__builtin_amdgcn_readlane((int)accs, k - 1);
+    // The sentence's best score images, lane i = i-th best, from the waves' lists.  With eight
+    // waves two share a SIMD, and the join is the same work in every wave: the first four (one
+    // per SIMD) do it and hand the outcome to the others.
+    constexpr int kJoiners = MW < 4 ? MW : 4;
+    uint32_t tau_s = 0;
     bool settled = true;
-    if (tau_s != 0) {
-        settled = (int)__popcll(__ballot(accs >= tau_s)) == k;  // places k.. hold lower scores
-        if (settled && k == kWave) {
-            // every place is taken: a tie may hide among the keys the merges dropped
-            for (int w = 1; w < MW; ++w) {
-                const uint32_t f = sm.wf[(wave + w) & (MW - 1)][lane];
-                fell = fell > f ? fell : f;
+    int need = 0;                                          // places left for keys that tie at the bar's score
+    if (wave < kJoiners) {
+        accs = join_best64<MW>(sm.ws, wave, lane, fell);
+        tau_s = (uint32_t)__builtin_amdgcn_readlane((int)accs, k - 1);
+        if (tau_s != 0) {
+            settled = (int)__popcll(__ballot(accs >= tau_s)) == k;  // places k.. hold lower scores
+            if (settled && k == kWave) {
+                // every place is taken: a tie may hide among the keys the merges dropped
+                for (int w = 1; w < MW; ++w) {
+                    const uint32_t f = sm.wf[(wave + w) & (MW - 1)][lane];
+                    fell = fell > f ? fell : f;
+                }
+                settled = wave_max_u32(fell) < tau_s;
             }
-            settled = wave_max_u32(fell) < tau_s;
         }
+        need = k - __popcll(__ballot(accs > tau_s));
+        if (MW > kJoiners && tid == 0) {
+            sm.bar_score = tau_s;
+            sm.bar_need = settled ? -1 : need;
+        }
+    }
+    if (MW > kJoiners) {
+        __syncthreads();
+        tau_s = sm.bar_score;
+        need = sm.bar_need;
+        settled = need < 0;
     }
     // tau = what a selection-key body has to reach to be among the k best; 0 while fewer than
     // k finite sums exist, in which case every finite sum is among them.
     u64 tau = (u64)tau_s << fb;
     if (!settled) {                                        // the same decision in every wave
-        const int need = k - __popcll(__ballot(accs > tau_s));      // places left for the tied keys
         const uint32_t low_bias = fb < 32 ? 1u : 0u;
         uint32_t unused = 0;
         uint32_t accl = wave_best64<kRowsPerWave, MW, true>(wave, k, need - 1, [&](int i) {
@@ -961,7 +988,7 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
             const uint32_t moved = (uint32_t)__shfl((int)lo, (lane + first) & (kWave - 1), kWave);
             return lane + first < kWave ? moved : 0u;
         }, unused);
-        accl = block_best64<MW, true>(sm.ws2, wave, lane, accl, unused);
+        accl = block_best64_sparse<MW>(sm.ws2, wave, lane, accl, unused);
         const uint32_t tau_l = (uint32_t)__builtin_amdgcn_readlane((int)accl, need - 1);
         tau = ((u64)tau_s << fb) | (u64)(tau_l - low_bias);
     }
