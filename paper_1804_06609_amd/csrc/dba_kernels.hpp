@@ -120,6 +120,7 @@ struct MergeSmem {
     uint32_t ws2[kMergeWavesMax][kWave];     // every wave's best low words among tied keys
     HypState hyp[kMaxBeam];
     u64 sel[kMaxBeam];
+    int slot[kMaxBeam];               // place in the new beam of the selected key i
     ConsTab ct;
     u64 fbucket[kMaxCons];            // phrases by the low six bits of their first token
     int btok[kMaxCons];               // and that token where a bucket's phrases agree on it (-1 none, -2 they differ)
@@ -1146,16 +1147,24 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
     __syncthreads();
 
     // ---- new beam, best first (Sec. 3.1); empty slots last ---------------------------------
+    // One lane per selected candidate.  Its place in the new beam is the number of selected keys greater
+    // than its own (at most 64 uniform LDS reads: cheaper than a 64-lane sort); wave 1 counts that
+    // while wave 0 takes the hypotheses through add().
     const int nsel = min(sm.nsel, k);
+    const bool live = lane < nsel;
+    const u64 mine = (wave <= 1 && live) ? sm.sel[lane] : 0ull;
+    if (wave == 1) {
+        int slot = 0;
+        for (int j = 0; j < nsel; j += 4)                 // (kMaxBeam is a multiple of 4; unused places hold 0)
+            slot += (sm.sel[j] > mine ? 1 : 0) + (sm.sel[j + 1] > mine ? 1 : 0) + (sm.sel[j + 2] > mine ? 1 : 0) +
+                    (sm.sel[j + 3] > mine ? 1 : 0);
+        sm.slot[lane] = slot;
+    }
+    int token = p.pad_id, parent = -1, length = 0, ipq2 = -1, nxt2 = -1;
+    float score = -INFINITY;
+    u64 met2 = 0, inc2 = 0;
+    uint8_t flags = 2, fin2 = 0;
     if (wave == 0) {
-        // one lane per selected candidate; its place in the new beam is the number of selected
-        // keys greater than its own (at most 64 uniform LDS reads: cheaper than a 64-lane sort)
-        const bool live = lane < nsel;
-        const u64 mine = live ? sm.sel[lane] : 0ull;
-        int token = p.pad_id, parent = -1, length = 0, ipq2 = -1, nxt2 = -1;
-        float score = -INFINITY;
-        u64 met2 = 0, inc2 = 0;
-        uint8_t flags = 2, fin2 = 0;
         if (live) {
             const uint32_t code = flatmask - ((uint32_t)mine & flatmask);
             parent = (int)(code >> p.tok_bits);
@@ -1211,10 +1220,10 @@ __device__ __forceinline__ void merge_phase(const StepParams &p, const u64 *rowl
             // division, the length counts end-of-sentence); it competed with its raw sum above
             if (p.normalize && fin2 && !pfin) score = __fdiv_rn(score, (float)length);
         }
-        int slot = 0;
-        for (int j = 0; j < nsel; j += 4)                 // (kMaxBeam is a multiple of 4; unused places hold 0)
-            slot += (sm.sel[j] > mine ? 1 : 0) + (sm.sel[j + 1] > mine ? 1 : 0) + (sm.sel[j + 2] > mine ? 1 : 0) +
-                    (sm.sel[j + 3] > mine ? 1 : 0);
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int slot = sm.slot[lane];
         // Sec. 4 / Sec. 6.3: hypotheses, completed or not, below (best completed - threshold) leave
         // the beam; the others close ranks
         bool keep = live;
