@@ -37,8 +37,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 # rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (scaled against a plain copy), and
 # the digest of the kernel sources those counters were taken with: the line carries the figure only
 # while the sources are still those, null otherwise.
-TRAFFIC_BYTES_PER_LAUNCH = 168780798
-TRAFFIC_KERNEL_SHA16 = "ed0148b4316cf6bd"
+TRAFFIC_BYTES_PER_LAUNCH = 168729167
+TRAFFIC_KERNEL_SHA16 = "fcace5d29b7358dc"
 
 
 def kernel_sources_sha16() -> str:
@@ -98,15 +98,15 @@ def timed_steps(wl, dev, K, W, dlen, repeats, options=None):
 _DECODE_STREAMS = []
 
 
-def concurrent_decodes(wl, dev, K, W, dlen, repeats, n_decodes):
+def concurrent_decodes(wl, dev, K, W, dlen, repeats, n_decodes, options=None):
     """Several independent decodes of the same workload in flight at once, each context on a stream of
     its own (default priority): what a server with more than one batch to translate does.  A step still
     depends on the step before it of the same decode, but one decode's per-sentence merge and launch
     latencies are filled with another decode's streaming.  So that the host's launch rate (Python) does
     not limit three decodes, the K steps of every decode are recorded beforehand into a HIP graph of
     its own (kernel nodes only) and the timed region launches the graphs side by side; if recording
-    fails the steps are enqueued in turn instead.  Returns (median wall-clock microseconds per step,
-    all decodes together; how the steps were submitted)."""
+    fails the steps are enqueued in turn instead.  options: dba_set_option settings of every context.
+    Returns (median wall-clock microseconds per step, all decodes together; how the steps were submitted)."""
     import torch
     from paper_1804_06609_amd.session import Session
     toks, poff, soff = wl.csr()
@@ -118,7 +118,7 @@ def concurrent_decodes(wl, dev, K, W, dlen, repeats, n_decodes):
     how = "one HIP graph per decode"
     for _ in range(repeats):
         n_dec = (W + K + dlen - 1) // dlen
-        ses = [[Session(wl.B, wl.k, wl.V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff, stream=st)
+        ses = [[Session(wl.B, wl.k, wl.V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff, stream=st, options=options)
                 for _ in range(n_dec)] for st in streams]
         torch.cuda.synchronize()
 
@@ -162,7 +162,8 @@ def concurrent_decodes(wl, dev, K, W, dlen, repeats, n_decodes):
     if not per_step:                             # recording failed in the first repeat: eager throughout
         for _ in range(repeats):
             n_dec = (W + K + dlen - 1) // dlen
-            ses = [[Session(wl.B, wl.k, wl.V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff, stream=st)
+            ses = [[Session(wl.B, wl.k, wl.V, dlen, wl.eos_id, wl.pad_id, toks, poff, soff, stream=st,
+                            options=options)
                     for _ in range(n_dec)] for st in streams]
             for g in range(W):
                 for i in range(n_decodes):
@@ -409,13 +410,19 @@ def main():
 
     # more than one decode in flight: the same kernels, the serial chain of one decode hidden by another
     if args.config == 4 and esize == 4 and not args.no_concurrent and args.cons_tokens is None:
-        cd = {}
-        for n in (2, 3):
-            us, how = concurrent_decodes(wl, dev, max(K, 200), W, dlen, max(3, args.repeats), n)
-            cd[str(n)] = {"us_per_step": us, "steps_per_s": 1e6 / us, "GBps": 4.0 * B * k * V / us / 1e3,
-                          "frac_of_hbm_peak": 4.0 * B * k * V / us / 1e3 / HBM_PEAK_GBS, "submission": how}
+        from paper_1804_06609_amd import DBA_OPT_MERGE_WAVES
+
+        def leg(n, options):
+            us, how = concurrent_decodes(wl, dev, max(K, 200), W, dlen, max(3, args.repeats), n, options)
+            return {"us_per_step": us, "steps_per_s": 1e6 / us, "GBps": 4.0 * B * k * V / us / 1e3,
+                    "frac_of_hbm_peak": 4.0 * B * k * V / us / 1e3 / HBM_PEAK_GBS, "submission": how}
+
+        cd = {str(n): leg(n, None) for n in (2, 3)}
+        cd["four_wave_merge"] = {str(n): leg(n, {DBA_OPT_MERGE_WAVES: 4}) for n in (2, 3)}
         cd["what"] = ("aggregate over 2 / 3 independent config-4 decodes, each context on a stream of its own (wall "
-                      "clock); `value` and `roofline` above are ONE decode, whose every step waits for the one before")
+                      "clock); `value` and `roofline` above are ONE decode, whose every step waits for the one before. "
+                      "four_wave_merge: the same with DBA_OPT_MERGE_WAVES = 4 (smaller workgroups in the second "
+                      "launch, placed more easily on a busy GPU; the default is chosen for one decode)")
         out["concurrent_decodes"] = cd
 
     if args.copy_probe:

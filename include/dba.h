@@ -204,11 +204,19 @@ DBA_API int dba_get_state(dba_ctx *ctx, float *score_host, uint64_t *met_mask_ho
  *                               hypothesis seen on any beam so far - ranked by score per word, a tie
  *                               keeps the earliest step, then the lowest slot - and dba_finalize
  *                               returns it (Sec. 3.3: the answer is the best-scoring finished hypothesis).
+ *   DBA_OPT_MERGE_WAVES         0 (default), 4 or 8 (anything else: DBA_EINVAL): wavefronts of the
+ *                               workgroup that handles one sentence in the second launch of a step.
+ *                               The results are the same for every setting; only the time differs.
+ *                               0 lets the library choose for the shortest step of a single decode
+ *                               (four up to k = 16, eight beyond).  Four-wave workgroups are placed more
+ *                               easily on a GPU that is busy with other work: the better setting where
+ *                               several decodes are in flight on the same GPU.
  */
 #define DBA_OPT_ADJUSTMENT 2
 #define DBA_OPT_NORMALIZE_FINISHED 3
 #define DBA_OPT_PRUNE_THRESHOLD 4
 #define DBA_OPT_TRACK_COMPLETED 5
+#define DBA_OPT_MERGE_WAVES 6
 DBA_API int dba_set_option(dba_ctx *ctx, int option, double value);
 
 /*

@@ -23,6 +23,7 @@ DBA_LOGP_F32, DBA_LOGP_F16, DBA_LOGP_BF16 = 0, 1, 2
 DBA_STOP_ALL, DBA_STOP_ANY = 1, 2
 DBA_OPT_ADJUSTMENT, DBA_OPT_NORMALIZE_FINISHED, DBA_OPT_PRUNE_THRESHOLD = 2, 3, 4
 DBA_OPT_TRACK_COMPLETED = 5
+DBA_OPT_MERGE_WAVES = 6
 
 _P = ctypes.c_void_p
 _I = ctypes.c_int

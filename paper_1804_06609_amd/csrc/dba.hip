@@ -450,6 +450,7 @@ struct dba_ctx {
     int normalize;                      // DBA_OPT_NORMALIZE_FINISHED
     float prune;                        // DBA_OPT_PRUNE_THRESHOLD (< 0: off)
     int track;                          // DBA_OPT_TRACK_COMPLETED
+    int merge_waves;                    // DBA_OPT_MERGE_WAVES (0: chosen here)
     int device;                         // the device that was current at dba_init
     unsigned char *lib_scratch;         // this device's copy of the library's own scratch (null: not resolved)
     size_t dyn_smem;
@@ -594,6 +595,7 @@ static int init_impl(dba_ctx **out, int B, int k, int V, int N, int eos_id, int 
     c->normalize = 0;
     c->prune = -1.0f;
     c->track = 0;
+    c->merge_waves = 0;
     c->device = -1;
     (void)hipGetDevice(&c->device);
     void *own = nullptr;
@@ -748,16 +750,22 @@ static int step_impl(dba_ctx *c, const void *logp_dev, int logp_format, int32_t 
             }
         }
         // The merge phase is compiled for (rows per wave, waves): the beam rows of a sentence are dealt out to
-        // the waves of its workgroup.  Four waves of four rows up to k = 16; from there on eight waves (of four
-        // rows up to k = 32, of eight beyond): fewer lists per wave to merge and to scan, a wave of its own
-        // for every chunk of candidates, at the price of a deeper tree where the waves' lists are joined
-        // (measured on MI355X: 6.2 / 6.5 us with four / eight waves at k = 10, 7.7 / 7.4 at k = 20, 19.3 / 15.4
-        // at k = 64).
+        // the waves of its workgroup.  Unless the caller fixes the waves: four waves of four rows up to k = 16;
+        // from there on eight waves (of four rows up to k = 32, of eight beyond): fewer lists per wave to merge
+        // and to scan, a wave of its own for every chunk of candidates, at the price of a deeper tree where the
+        // waves' lists are joined (measured on MI355X, one decode: 6.2 / 6.5 us with four / eight waves at
+        // k = 10, 7.7 / 7.0 at k = 20, 19.3 / 14.6 at k = 64).
         const dim3 mgrid((unsigned)c->B);
         const dim3 mblock8(8 * kWave), mblock4(4 * kWave);
-        if (c->k <= 16) dba_merge_kernel<4, 4><<<mgrid, mblock4, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
-        else if (c->k <= 32) dba_merge_kernel<4, 8><<<mgrid, mblock8, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
-        else dba_merge_kernel<8, 8><<<mgrid, mblock8, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+        const int mw = c->merge_waves ? c->merge_waves : (c->k <= 16 ? 4 : 8);
+        if (mw == 4) {
+            if (c->k <= 16) dba_merge_kernel<4, 4><<<mgrid, mblock4, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+            else if (c->k <= 32) dba_merge_kernel<8, 4><<<mgrid, mblock4, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+            else dba_merge_kernel<16, 4><<<mgrid, mblock4, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+        } else {
+            if (c->k <= 32) dba_merge_kernel<4, 8><<<mgrid, mblock8, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+            else dba_merge_kernel<8, 8><<<mgrid, mblock8, c->dyn_smem, c->stream>>>(p.rowlists, p.conskeys, p.k, p);
+        }
     }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, DBA_EHIP, "dba_step: launch failed: %s", hipGetErrorString(e));
@@ -876,6 +884,11 @@ DBA_API int dba_set_option(dba_ctx *c, int option, double value)
         case DBA_OPT_NORMALIZE_FINISHED: c->normalize = value != 0.0 ? 1 : 0; return DBA_OK;
         case DBA_OPT_PRUNE_THRESHOLD: c->prune = value < 0.0 ? -1.0f : (float)value; return DBA_OK;
         case DBA_OPT_TRACK_COMPLETED: c->track = value != 0.0 ? 1 : 0; return DBA_OK;
+        case DBA_OPT_MERGE_WAVES:
+            if (value != 0.0 && value != 4.0 && value != 8.0)
+                return fail(c, DBA_EINVAL, "dba_set_option: DBA_OPT_MERGE_WAVES takes 0, 4 or 8");
+            c->merge_waves = (int)value;
+            return DBA_OK;
         default: return fail(c, DBA_EINVAL, "dba_set_option: unknown option %d", option);
     }
 }

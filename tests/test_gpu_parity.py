@@ -350,7 +350,7 @@ def test_option_combinations_fuzz(torch_gpu, block):
     """Sixty small decodes in which everything varies at once: shape (k = 1..64, V = 37..9001), phrase
     count and length, repeated tokens, when end-of-sentence becomes likely, the element type of the
     log-probs, and every combination of the options (adjustment, per-word scores, pruning threshold,
-    record of completed hypotheses)."""
+    record of completed hypotheses), and the waves of the merge phase's workgroups."""
     for seed in range(10 * block, 10 * block + 10):
         rs = si.Stream(seed, 77)
         B = rs.randint(1, 6)
@@ -361,9 +361,22 @@ def test_option_combinations_fuzz(torch_gpu, block):
                            dup_prob=[0.0, 0.35, 0.7][seed % 3])
         wl.eos_switch = rs.randint(2, T)
         wl.eos_high = [0.5, 2.0, 3.0][seed % 3]
+        import paper_1804_06609_amd as dba
         _harness().run_parity(wl, adjust=bool(seed & 1), normalize=bool(seed & 2),
                               prune=[None, 20.0, 2.0, 0.0][(seed >> 2) & 3], track=bool(seed & 16),
-                              logp_format=[None, None, "bf16", "f16"][(seed // 2) % 4])
+                              logp_format=[None, None, "bf16", "f16"][(seed // 2) % 4],
+                              options={dba.DBA_OPT_MERGE_WAVES: [0, 4, 8][(seed // 5) % 3]})
+
+
+@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("cfg,T,B", [(2, 20, None), (4, 30, 12), (5, 14, 3)])
+def test_merge_phase_with_four_and_with_eight_waves(torch_gpu, cfg, T, B, waves):
+    """DBA_OPT_MERGE_WAVES changes how a sentence's beam rows are dealt out to the waves of its
+    workgroup in the second launch, never the result: k = 10, 20 and 64 (configs 2, 4 and 5, a few
+    sentences, the first steps - where the candidates are most) with both fixed settings."""
+    import paper_1804_06609_amd as dba
+    wl = si.make_config(cfg, T=T) if B is None else si.make_config(cfg, T=T, B=B)
+    _harness().run_parity(wl, options={dba.DBA_OPT_MERGE_WAVES: waves})
 
 
 def test_paper_setup_config2(torch_gpu):
@@ -557,6 +570,8 @@ def test_call_order_errors(torch_gpu):
     dev = torch_gpu.from_numpy(wl.logp(0)).cuda()
     with pytest.raises(dba.DbaError, match="unknown option"):
         dba.dba_set_option(ses.ctx, 9999, 1)
+    with pytest.raises(dba.DbaError):
+        dba.dba_set_option(ses.ctx, dba.DBA_OPT_MERGE_WAVES, 5)
     with pytest.raises(dba.DbaError, match="unknown log-prob format"):
         dba.dba_step_fmt(ses.ctx, dev.data_ptr(), 7)
     with pytest.raises(dba.DbaError, match="aligned"):
